@@ -1,0 +1,161 @@
+#!/usr/bin/env python3
+"""Benchmark of the f16 GEMM hot path on one MI355X.
+
+A step is one call of gemm_f16_f32acc on the headline workload (M = N = K =
+8192, A and B ~ N(0,1)/sqrt(K) in f16, C f32 starting at zero and accumulating
+over the steps): C tile -> accumulators, global -> LDS staging, MFMA main loop,
+store.  Inputs are resident in HBM before the timed region.  Prints ONE JSON
+line: TFLOP/s = 2 M N K / time, the roofline of the kernel measured with HIP
+events on the launch stream, and the CPU oracle timed on a bounded row sample.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+                    [--mode f32|f16] [--no-cpu] [--sweep]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_F16_MFMA_TFLOPS = 2516.6      # 256 CU x 4096 flop/clk/CU x 2.4 GHz, dense
+PEAK_HBM_GBS = 8000.0
+
+
+def algorithmic_bytes(M, N, K, c_bytes):
+    """A and B read once (f16), C read once and written once."""
+    return 2 * (M * K + K * N) + 2 * M * N * c_bytes
+
+
+def time_gemm(binding, torch, mode, M, N, K, dA, dB, dC, steps, warmup):
+    """Return (ms per step over the timed region, list of per-launch ms)."""
+    fn = binding.gemm_f16_f32acc if mode == "f32" else binding.gemm_f16_f16acc
+    stream = torch.cuda.current_stream()
+    sp = stream.cuda_stream
+    lda, ldb, ldc = dA.stride(0), dB.stride(0), dC.stride(0)
+    for _ in range(warmup):
+        binding.check(fn(M, N, K, dA, lda, dB, ldb, dC, ldc, sp))
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    evs[0].record(stream)
+    for i in range(steps):
+        binding.check(fn(M, N, K, dA, lda, dB, ldb, dC, ldc, sp))
+        evs[i + 1].record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    per = [evs[i].elapsed_time(evs[i + 1]) for i in range(steps)]
+    total = evs[0].elapsed_time(evs[steps])
+    return total / steps, per, wall_ms / steps
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="sq8192_normal")
+    ap.add_argument("--mode", default="f32", choices=["f32", "f16"])
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--cpu-rows", type=int, default=768, help="rows of C the oracle is timed on")
+    ap.add_argument("--sweep", action="store_true", help="also time every workload and the square sweep (extra lines on stderr)")
+    ap.add_argument("--force-config", type=int, default=-1)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2108_13191_amd import binding, workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    binding.load()
+    binding.force_config(args.force_config)
+    dev = torch.device("cuda:0")
+
+    def run_workload(name, mode, steps, warmup, shape=None):
+        if shape is None:
+            M, N, K, dab, dc, _ = wl.WORKLOADS[name]
+        else:
+            M, N, K, dab, dc = (*shape, "uniform", "zeros")
+        cdt = np.float32 if mode == "f32" else np.float16
+        A, B, C0 = wl.make_inputs(M, N, K, dab, dc, seed=0, c_dtype=cdt)
+        dA, dB, dC = (torch.from_numpy(x).to(dev) for x in (A, B, C0))
+        ms, per, wall = time_gemm(binding, torch, mode, M, N, K, dA, dB, dC, steps, warmup)
+        cfg = binding.query_config(mode == "f16", M, N, K, dA, dA.stride(0), dB, dB.stride(0), dC, dC.stride(0))
+        flops = 2.0 * M * N * K
+        return dict(M=M, N=N, K=K, ms=ms, per=per, wall_ms=wall, tflops=flops / (ms * 1e-3) / 1e12, cfg=cfg,
+                    bytes=algorithmic_bytes(M, N, K, 4 if mode == "f32" else 2)), (A, B, C0)
+
+    r, (A, B, C0) = run_workload(args.workload, args.mode, args.steps, args.warmup)
+    M, N, K = r["M"], r["N"], r["K"]
+    per = sorted(r["per"])
+    avg_launch_ms = sum(per) / len(per)
+    achieved = 2.0 * M * N * K / (avg_launch_ms * 1e-3) / 1e12
+    t_mfma = 2.0 * M * N * K / (PEAK_F16_MFMA_TFLOPS * 1e12)
+    t_hbm = r["bytes"] / (PEAK_HBM_GBS * 1e9)
+    if t_mfma >= t_hbm:
+        roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_F16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(achieved / PEAK_F16_MFMA_TFLOPS, 4), "traffic": None}
+    else:
+        gbs = r["bytes"] / (avg_launch_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None}
+    roofline.update({"kernel": "gemm_tiled_kernel<" + r["cfg"]["name"] + ">", "avg_launch_ms": round(avg_launch_ms, 5),
+                     "median_launch_ms": round(per[len(per) // 2], 5), "min_launch_ms": round(per[0], 5),
+                     "algorithmic_bytes": r["bytes"], "flops": 2 * M * N * K})
+
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        nrows = min(args.cpu_rows, M)
+        rows = np.arange(nrows, dtype=np.int64)
+        t0 = time.perf_counter()
+        oracle.gemm_f16(A, B, C0, rows=rows)
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(2.0 * nrows * N * K / dt / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+               "kind": "oracle", "seconds": round(dt, 2),
+               "sample": f"first {nrows} of {M} rows of C (all {N} columns, full K={K}) of the same workload, "
+                         f"binary64 triple loop incl. decoding B; host has {os.cpu_count()} logical CPUs"}
+
+    out = {
+        "metric": "TFLOP/s (2MNK/time), f16 GEMM " + ("f32" if args.mode == "f32" else "f16") + "-accumulate, M=N=K=8192"
+                  if args.workload == "sq8192_normal" else f"TFLOP/s (2MNK/time), f16 GEMM {args.mode}-accumulate",
+        "value": round(r["tflops"], 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(r["ms"], 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 inputs, f32 accumulate" + ("" if args.mode == "f32" else ", f16 store"),
+        "data": "synthetic", "pct_of_f16_mfma_peak": round(100 * r["tflops"] / PEAK_F16_MFMA_TFLOPS, 2),
+        "config": {"workload": f"{args.workload}: M={M} N={N} K={K}, mode {args.mode}", "tile": r["cfg"]["name"],
+                   "grid": r["cfg"]["grid"], "host_wall_ms_per_step": round(r["wall_ms"], 5)},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+
+    if args.sweep:
+        extra = []
+        for name, (m, n, k, _, _, modes) in wl.WORKLOADS.items():
+            for mode in modes:
+                rr, _ = run_workload(name, mode, 20, 5)
+                extra.append({"workload": name, "mode": mode, "M": m, "N": n, "K": k, "ms": round(rr["ms"], 5),
+                              "tflops": round(rr["tflops"], 1), "pct_peak": round(100 * rr["tflops"] / PEAK_F16_MFMA_TFLOPS, 1),
+                              "gbs": round(rr["bytes"] / (rr["ms"] * 1e-3) / 1e9, 1), "tile": rr["cfg"]["name"]})
+                print(json.dumps(extra[-1]), file=sys.stderr, flush=True)
+        for n in wl.SQUARE_SWEEP:
+            for mode in ("f32", "f16"):
+                rr, _ = run_workload(None, mode, 10 if n > 8192 else 20, 3, shape=(n, n, n))
+                extra.append({"workload": f"square{n}", "mode": mode, "M": n, "N": n, "K": n, "ms": round(rr["ms"], 5),
+                              "tflops": round(rr["tflops"], 1), "pct_peak": round(100 * rr["tflops"] / PEAK_F16_MFMA_TFLOPS, 1),
+                              "gbs": round(rr["bytes"] / (rr["ms"] * 1e-3) / 1e9, 1), "tile": rr["cfg"]["name"]})
+                print(json.dumps(extra[-1]), file=sys.stderr, flush=True)
+        out["sweep"] = extra
+
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

