@@ -7,15 +7,18 @@
 
 namespace {
 
-// Configuration table: entry 0 is the any-shape kernel, the rest are the
-// tuned ones.
-int num_configs() { return 1 + tiled_num_configs(); }
+// Configuration table: entry 0 is the any-shape kernel, entry 1 the 256 x 256
+// phase-alternating kernel, the rest the plain double-buffered ones.
+int num_configs() { return 2 + tiled_num_configs(); }
 
 const GemmConfigDesc kGeneric = {
     "generic64x64x32", 64, 64, 32, 4, 32, 32, 2 * 64 * (32 + 8) * 2,
     false, launch_generic, grid_generic};
 
-const GemmConfigDesc* config(int id) { return id == 0 ? &kGeneric : tiled_config(id - 1); }
+const GemmConfigDesc* config(int id)
+{
+    return id == 0 ? &kGeneric : id == 1 ? pingpong_config() : tiled_config(id - 2);
+}
 
 int g_forced = -1;
 
@@ -36,8 +39,8 @@ bool aligned_for_tiled(int64_t N, int64_t K, const void* A, int64_t lda, const v
 {
     return ((uintptr_t)A % 16 == 0) && ((uintptr_t)B % 16 == 0) && lda % 8 == 0 && ldb % 8 == 0 &&
            K % 8 == 0 && N % 8 == 0 && K >= 8 &&
-           // tile-relative byte offsets are formed in 64 bits, but keep rows sane
-           lda <= (1 << 28) && ldb <= (1 << 28);
+           // tile-relative byte offsets (up to 256 rows) are kept in 32 bits
+           lda <= (1 << 22) && ldb <= (1 << 22);
 }
 
 // Pick the configuration with the lowest estimated time.  The estimate is the
@@ -50,8 +53,8 @@ int select_config(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, c
     if (!aligned_for_tiled(N, K, A, lda, B, ldb)) return 0;
     if (g_forced >= 0 && g_forced < num_configs()) return g_forced;
     struct Cand { int id; double eff; int per_cu; };
-    // ids: 1 = 256x256 (8 waves), 3 = 128x128, 4 = 64x64
-    const Cand cands[] = {{1, 1.0, 1}, {3, 0.8, 2}, {4, 0.5, 4}};
+    // ids: 1 = 256x256 phase-alternating, 4 = 128x128, 5 = 64x64
+    const Cand cands[] = {{1, 1.0, 1}, {4, 0.7, 2}, {5, 0.4, 4}};
     int best = 1;
     double best_cost = 0;
     for (const Cand& c : cands) {

@@ -41,3 +41,6 @@ int64_t grid_generic(int64_t M, int64_t N);
 // gemm_tiled.hip
 int tiled_num_configs();
 const GemmConfigDesc* tiled_config(int i);
+
+// gemm_pingpong.hip
+const GemmConfigDesc* pingpong_config();

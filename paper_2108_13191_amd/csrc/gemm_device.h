@@ -1,0 +1,115 @@
+// Device-side helpers shared by the tuned kernels (gemm_tiled.hip,
+// gemm_pingpong.hip): the direct global -> LDS copy, the two LDS fragment
+// reads, the XCD-aware workgroup -> tile map.  gfx950 only.
+#pragma once
+#include "gemm_common.h"
+
+namespace gemm_dev {
+
+constexpr int BK = 64;             // k extent per LDS stage (f16 elements)
+constexpr int NUM_XCD = 8;
+
+struct TiledParams {
+    int M, N, K;
+    const half_t* A; int64_t lda;
+    const half_t* B; int64_t ldb;
+    void* C; int64_t ldc;
+    int tiles_m, tiles_n, group_m;
+};
+
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef __attribute__((address_space(1))) const void* gbl_ptr_t;
+typedef __attribute__((address_space(3))) shortx4* lds_s4_ptr_t;
+
+// 16 bytes per lane, global -> LDS at lds_byte_addr (wave-uniform) + 16 * lane.
+// The global address is base (wave-uniform, 64 bit) + byte_off (per lane, 32
+// bit).  Written as inline assembly on purpose: the compiler cannot tell which
+// LDS bytes an LDS-DMA load writes and would wait for ALL outstanding copies
+// (vmcnt(0)) in front of every LDS read of the other buffer, serialising the
+// prefetch with the MFMA phase.  The kernel orders these copies itself: an
+// explicit vmcnt(0) and a barrier before a buffer is read.
+__device__ __forceinline__ void async_copy16(const void* base, uint32_t byte_off, uint32_t lds_byte_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\t"
+                 "s_nop 0\n\t"
+                 "global_load_lds_dwordx4 %0, %1"
+                 :: "v"(byte_off), "s"(base), "s"(lds_byte_addr) : "memory", "m0");
+}
+
+__device__ __forceinline__ half8 lds_read_b128(uint32_t addr)
+{
+    return *(__attribute__((address_space(3))) const half8*)(uintptr_t)addr;
+}
+
+__device__ __forceinline__ half4 lds_read_tr16(uint32_t addr)
+{
+    shortx4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr_t)(uintptr_t)addr);
+    return __builtin_bit_cast(half4, v);
+}
+
+// Workgroup id -> C tile.  Ids are dealt to the XCDs round-robin; give XCD x
+// the x-th contiguous slice of a tile order that walks group_m tile rows at a
+// time, column by column.
+__device__ __forceinline__ void tile_of_block(const TiledParams& p, int pid, int& tile_m, int& tile_n)
+{
+    const int num = p.tiles_m * p.tiles_n;
+    const int q = num / NUM_XCD, r = num % NUM_XCD;
+    const int x = pid % NUM_XCD;
+    const int l = x * q + (x < r ? x : r) + pid / NUM_XCD;
+    const int group_size = p.group_m * p.tiles_n;
+    const int g = l / group_size;
+    const int first_m = g * p.group_m;
+    const int gm = (p.tiles_m - first_m < p.group_m) ? (p.tiles_m - first_m) : p.group_m;
+    const int in_group = l % group_size;
+    tile_m = first_m + in_group % gm;
+    tile_n = in_group / gm;
+}
+
+// C tile <-> accumulators of one wavefront: FM x FN blocks of 32 x 32, block
+// (fm, fn) at rows row0 + 32 fm, columns col0 + 32 fn (row0, col0 wave-uniform).
+// Accumulator register i of lane l is row 8*(i/4) + 4*(l/32) + i%4, column l%32
+// of its block.  Addresses are a wave-uniform row pointer plus one per-lane
+// 32-bit offset, so that no per-element 64-bit address lives in registers.
+// With `edge`, elements at rows >= M or columns >= N are read as 0 / not stored.
+template <typename CT, int FM, int FN>
+__device__ __forceinline__ void load_c_tile(floatx16 (&acc)[FM][FN], const CT* C, int64_t ldc,
+                                            int row0, int col0, int lane, int M, int N, bool edge)
+{
+    const uint32_t voff = ((uint32_t)(4 * (lane >> 5)) * (uint32_t)ldc + (uint32_t)(lane & 31)) * (uint32_t)sizeof(CT);
+    const int lrow = 4 * (lane >> 5), lcol = lane & 31;
+#pragma unroll
+    for (int fm = 0; fm < FM; fm++)
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            const int r = row0 + fm * 32 + 8 * (i / 4) + (i & 3);
+            const char* rowp = reinterpret_cast<const char*>(C + (int64_t)r * ldc + col0);
+#pragma unroll
+            for (int fn = 0; fn < FN; fn++) {
+                float v = 0.0f;
+                if (!edge || (r + lrow < M && col0 + fn * 32 + lcol < N))
+                    v = (float)*reinterpret_cast<const CT*>(rowp + voff + fn * 32 * sizeof(CT));
+                acc[fm][fn][i] = v;
+            }
+        }
+}
+
+template <typename CT, int FM, int FN>
+__device__ __forceinline__ void store_c_tile(const floatx16 (&acc)[FM][FN], CT* C, int64_t ldc,
+                                             int row0, int col0, int lane, int M, int N, bool edge)
+{
+    const uint32_t voff = ((uint32_t)(4 * (lane >> 5)) * (uint32_t)ldc + (uint32_t)(lane & 31)) * (uint32_t)sizeof(CT);
+    const int lrow = 4 * (lane >> 5), lcol = lane & 31;
+#pragma unroll
+    for (int fm = 0; fm < FM; fm++)
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            const int r = row0 + fm * 32 + 8 * (i / 4) + (i & 3);
+            char* rowp = reinterpret_cast<char*>(C + (int64_t)r * ldc + col0);
+#pragma unroll
+            for (int fn = 0; fn < FN; fn++)
+                if (!edge || (r + lrow < M && col0 + fn * 32 + lcol < N))
+                    *reinterpret_cast<CT*>(rowp + voff + fn * 32 * sizeof(CT)) = (CT)acc[fm][fn][i];   // f16: one rounding, to nearest even
+        }
+}
+
+}  // namespace gemm_dev

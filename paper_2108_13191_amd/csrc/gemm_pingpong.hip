@@ -1,0 +1,316 @@
+// The large-problem kernel: 256 x 256 C tile per workgroup, 8 wavefronts, k
+// steps of 64, f16 MFMA (v_mfma_f32_32x32x16_f16) with f32 accumulators.
+//
+// The steps are those of the paper's recipe (Algorithm "Two-level tiled tensor
+// core Matmul"; C hoisted out of the k loop, section "Generating WMMA Ops and
+// More"; global loads for later k tiles in flight while the current one is
+// multiplied, section "Completing Latency Hiding"), arranged for CDNA4:
+//
+//   * Wavefronts 0-3 ("X") own the top 128 rows of the tile, 4-7 ("Y") the
+//     bottom 128; each owns a 128 x 64 block (4 x 2 accumulators of 32 x 32,
+//     128 registers).  Wavefront w and w+4 share a SIMD.
+//   * Time is cut into phases separated by one workgroup barrier.  In a phase
+//     one group reads its A/B fragments of half a k step from LDS into
+//     registers (48 VGPRs) and issues global -> LDS copies, while the other
+//     group issues its 16 MFMAs back to back with every operand already in
+//     registers; then they swap.  The matrix pipe of a SIMD therefore always
+//     has a wavefront that is not waiting on memory.
+//   * 160 KB of LDS hold 2 A buffers (256 x 64 f16 = 32 KB each) and 3 B
+//     buffers (64 x 256 f16 = 32 KB each).  Every copy is issued at least five
+//     phases before its data is read (A halves are recycled as soon as the
+//     group that owns those rows has read them; B needs the third buffer for
+//     that), so a copy has five MFMA phases to cross L2 / Infinity Fabric.
+//   * Copies are global_load_lds_dwordx4 (no register staging); the LDS image
+//     is XOR-swizzled by the choice of the chunk each lane fetches; A
+//     fragments are ds_read_b128, B fragments ds_read_b64_tr_b16 (B is
+//     N-contiguous, the MFMA wants K-contiguous lanes).
+//
+// Schedule (k = k step of 64, cut in halves h = 0,1 of two 16-wide k slices;
+// phase numbers P):
+//   X: P = 4k+2h    read the fragments of (k,h); h=0: issue A-bottom(k+1),
+//                   h=1: issue B-low(k+2)
+//      P = 4k+2h+1  16 MFMAs of (k,h)
+//   Y: the same one phase later; h=0: issue B-high(k+2), h=1: A-top(k+2)
+// ("low/high" = k rows 0-31 / 32-63 of a B stage).  At the end of a reading
+// phase a wavefront waits until the copies it issued two reading phases ago
+// have landed (vmcnt(8): only the 8 issued since may be outstanding), so data
+// is visible to everybody at least five phases after it was requested, and a
+// buffer is overwritten only after its last reader has passed a barrier.
+//
+// Requirements as for the other tuned kernels: A, B 16-byte aligned; lda, ldb,
+// K, N multiples of 8.  Rows >= M / columns >= N are fetched from clamped
+// addresses and never stored; the k tail is zero-filled through registers.
+#include "gemm_device.h"
+#include "../../include/gemm_f16.h"
+
+namespace {
+
+using namespace gemm_dev;
+
+constexpr int PBM = 256, PBN = 256;
+constexpr int A_BUF = PBM * BK * 2;          // 32 KB
+constexpr int B_BUF = BK * PBN * 2;          // 32 KB
+constexpr int A_REGION = 0;                  // two A buffers
+constexpr int B_REGION = 2 * A_BUF;          // three B buffers
+constexpr int PP_LDS = 2 * A_BUF + 3 * B_BUF;   // 160 KB
+constexpr int B_ROW = PBN * 2;               // bytes per k row of a B stage
+
+__device__ __forceinline__ void phase_barrier()
+{
+    // nothing may be scheduled across a phase boundary
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+template <typename CT>
+__global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
+{
+    __shared__ __attribute__((aligned(1024))) char smem[PP_LDS];
+    const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_ptr_t)smem;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = wave >> 2;                 // 0: X (top rows), 1: Y (bottom rows)
+    const int wn = wave & 3;                   // column block of 64; also the copy slot within the group
+
+    int tile_m, tile_n;
+    tile_of_block(p, blockIdx.x, tile_m, tile_n);
+    const int m0 = tile_m * PBM, n0 = tile_n * PBN;
+    const bool edge = (m0 + PBM > p.M) || (n0 + PBN > p.N);
+
+    const int kt_full = p.K / BK;
+    const int KT = (p.K + BK - 1) / BK;
+
+    // ---- copy plan ----------------------------------------------------------
+    // A half (128 rows x 128 B = 16 KB) = 16 wave-wide copies of 8 rows; the 4
+    // wavefronts of a group take copies q = wn + 4t.  Lane i writes (row
+    // 8q + i/8, chunk position i%8), which must hold logical chunk
+    // position ^ ((row/2)%8) -- a per-lane constant because q = wn (mod 2).
+    const half_t* const a_tile = p.A + (int64_t)m0 * p.lda;
+    const half_t* const b_tile = p.B + n0;
+    const int a_chunk = (lane & 7) ^ (4 * (wn & 1) + (lane >> 4));
+    auto a_offset = [&](int half, int t) -> uint32_t {
+        int row = half * 128 + 8 * (wn + 4 * t) + (lane >> 3);
+        row = (m0 + row < p.M) ? row : p.M - 1 - m0;                 // clamp: loaded, never stored
+        return ((uint32_t)row * (uint32_t)p.lda + 8 * a_chunk) * 2;
+    };
+    // B half (32 k rows x 512 B = 16 KB) = 16 copies of 2 k rows; lane i writes
+    // (k row 2q + i/32, chunk position i%32), which must hold the chunk whose
+    // 64-byte granule index is XORed with (k row)%4.
+    const int b_krow_in_copy = lane >> 5;
+    int b_col;
+    {
+        const int sw = 2 * (wn & 1) + (lane >> 5);                   // (2q + i/32) % 4
+        const int chunk = (lane & 31) ^ (sw << 2);
+        b_col = 8 * chunk;
+        if (n0 + b_col + 8 > p.N) b_col = 0;                         // clamp: loaded, never stored
+    }
+    auto b_offset = [&](int t) -> uint32_t {                          // relative to the half's first k row
+        return ((uint32_t)(2 * (wn + 4 * t) + b_krow_in_copy) * (uint32_t)p.ldb + b_col) * 2;
+    };
+
+    // one A half of k step s into A buffer s%2; `off` = the caller's 4 lane offsets
+    auto copy_a_half = [&](int s, int half, const uint32_t (&off)[4]) {
+        const uint32_t dst = smem_base + A_REGION + (s & 1) * A_BUF + half * (A_BUF / 2);
+        const half_t* src = a_tile + (int64_t)s * BK;
+        if (s < kt_full) {
+#pragma unroll
+            for (int t = 0; t < 4; t++) async_copy16(src, off[t], dst + 1024 * (wn + 4 * t));
+        } else {                                                       // k tail: through registers, zero beyond K
+            const int kvalid = p.K - s * BK;
+#pragma unroll
+            for (int t = 0; t < 4; t++) {
+                uintx4 v = {0u, 0u, 0u, 0u};
+                if (8 * a_chunk < kvalid) v = *reinterpret_cast<const uintx4*>((const char*)src + off[t]);
+                *(__attribute__((address_space(3))) uintx4*)(uintptr_t)(dst + 1024 * (wn + 4 * t) + 16 * lane) = v;
+            }
+        }
+    };
+    // one B half of k step s into B buffer s%3
+    auto copy_b_half = [&](int s, int half, const uint32_t (&off)[4]) {
+        const uint32_t dst = smem_base + B_REGION + (s % 3) * B_BUF + half * (B_BUF / 2);
+        const half_t* src = b_tile + ((int64_t)s * BK + half * 32) * p.ldb;
+        if (s < kt_full) {
+#pragma unroll
+            for (int t = 0; t < 4; t++) async_copy16(src, off[t], dst + 1024 * (wn + 4 * t));
+        } else {
+            const int kvalid = p.K - s * BK - half * 32;               // valid k rows of this half (may be <= 0)
+#pragma unroll
+            for (int t = 0; t < 4; t++) {
+                uintx4 v = {0u, 0u, 0u, 0u};
+                if (2 * (wn + 4 * t) + b_krow_in_copy < kvalid) v = *reinterpret_cast<const uintx4*>((const char*)src + off[t]);
+                *(__attribute__((address_space(3))) uintx4*)(uintptr_t)(dst + 1024 * (wn + 4 * t) + 16 * lane) = v;
+            }
+        }
+    };
+
+    // steady-state offsets: X copies A-bottom and B-low, Y copies A-top and B-high
+    uint32_t a_off[4], b_off[4];
+#pragma unroll
+    for (int t = 0; t < 4; t++) { a_off[t] = a_offset(1 - grp, t); b_off[t] = b_offset(t); }
+
+    // ---- prologue: everything the schedule does not cover -------------------
+    // X: A-bottom(0), B-low(0), B-low(1);  Y: A-top(0), A-top(1), B-high(0), B-high(1)
+    {
+        if (grp == 0) {
+            copy_a_half(0, 1, a_off);
+            copy_b_half(0, 0, b_off);
+            if (KT > 1) copy_b_half(1, 0, b_off);
+        } else {
+            copy_a_half(0, 0, a_off);
+            if (KT > 1) copy_a_half(1, 0, a_off);
+            copy_b_half(0, 1, b_off);
+            if (KT > 1) copy_b_half(1, 1, b_off);
+        }
+    }
+
+    // ---- C tile -> accumulators ---------------------------------------------
+    // accumulator register i of lane l: row 8*(i/4) + 4*(l/32) + i%4, column l%32
+    floatx16 acc[4][2];
+    CT* const Cbase = (CT*)p.C;
+    const int crow0 = m0 + grp * 128;
+    const int ccol0 = n0 + wn * 64;
+    load_c_tile<CT, 4, 2>(acc, Cbase, p.ldc, crow0, ccol0, lane, p.M, p.N, edge);
+
+    // ---- fragment read addresses ----------------------------------------------
+    // A operand: lane l holds tile row (l%32) of its 32-row block, k = 8*(l/32)..+7
+    // of the 16-wide slice ks -> logical chunk 2*ks + l/32, stored at chunk ^ ((row/2)%8).
+    uint32_t a_rd[4];
+    {
+        const uint32_t row_off = (uint32_t)(grp * 128 + (lane & 31)) * (BK * 2);
+        const int sw = (lane >> 1) & 7;
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++)
+            a_rd[ks] = smem_base + A_REGION + row_off + (uint32_t)(((2 * ks + (lane >> 5)) ^ sw) * 16);
+    }
+    // B operand: one transposing read serves 16 lanes -- lanes 4r..4r+3 of a
+    // 16-lane block point at 16 consecutive columns of k row r and lane i gets
+    // column i of rows 0..3.  Blocks 0,1: the two column halves at k 0..7,
+    // blocks 2,3: at k 8..15; two reads (k +0..3, +4..7) make one operand.
+    uint32_t b_rd[2];
+    {
+        const int blk = lane >> 4, j = lane & 15;
+        const uint32_t lane_off = (uint32_t)(8 * (blk >> 1) + (j >> 2)) * B_ROW + (uint32_t)(16 * (blk & 1) + 4 * (j & 3)) * 2;
+#pragma unroll
+        for (int fn = 0; fn < 2; fn++)
+            b_rd[fn] = smem_base + B_REGION + lane_off + (uint32_t)(((wn * 2 + fn) ^ (j >> 2)) * 64);
+    }
+
+    half8 fa[2][4], fb[2][2];      // fragments of half a k step (k slices 2h, 2h+1): [ks][fm], [ks][fn]
+
+    auto read_fragments = [&](int k, int h) {
+        const uint32_t a_buf = (uint32_t)(k & 1) * A_BUF;
+        const uint32_t b_buf = (uint32_t)(k % 3) * B_BUF;
+        // one address register per fragment column (fn) / k slice (ks); the
+        // rest of each address is an instruction offset
+        uint32_t b0[2];
+#pragma unroll
+        for (int fn = 0; fn < 2; fn++) { b0[fn] = b_rd[fn] + b_buf; asm volatile("" : "+v"(b0[fn])); }
+#pragma unroll
+        for (int s = 0; s < 2; s++) {
+            const int ks = 2 * h + s;
+            uint32_t a0 = a_rd[ks] + a_buf;
+            asm volatile("" : "+v"(a0));
+#pragma unroll
+            for (int fm = 0; fm < 4; fm++)
+                fa[s][fm] = lds_read_b128(a0 + fm * 32 * (BK * 2));
+#pragma unroll
+            for (int fn = 0; fn < 2; fn++) {
+                const half4 lo = lds_read_tr16(b0[fn] + ks * 16 * B_ROW);
+                const half4 hi = lds_read_tr16(b0[fn] + ks * 16 * B_ROW + 4 * B_ROW);
+                fb[s][fn] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+        }
+    };
+    auto multiply = [&]() {
+#pragma unroll
+        for (int s = 0; s < 2; s++)
+#pragma unroll
+            for (int fm = 0; fm < 4; fm++)
+#pragma unroll
+                for (int fn = 0; fn < 2; fn++)
+                    acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[s][fm], fb[s][fn], acc[fm][fn], 0, 0, 0);
+    };
+    // A reading phase for half h of k step k: 4 copies for a later step, the
+    // fragment reads, then wait for (a) the copies issued two reading phases
+    // ago (only the 8 issued since may be outstanding) and (b) the fragment
+    // reads, so that the barrier that follows publishes both.
+    auto reading_phase = [&](int k, int h) {
+        if (grp == 0) {
+            if (h == 0) { if (k + 1 < KT) copy_a_half(k + 1, 1, a_off); }
+            else        { if (k + 2 < KT) copy_b_half(k + 2, 0, b_off); }
+        } else {
+            if (h == 0) { if (k + 2 < KT) copy_b_half(k + 2, 1, b_off); }
+            else        { if (k + 2 < KT) copy_a_half(k + 2, 0, a_off); }
+        }
+        read_fragments(k, h);
+        if (k + 2 < kt_full) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    };
+
+    // prologue copies and the C tile have landed before phase 0
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    phase_barrier();
+
+    // Both groups run the same loop; Y enters it one phase (one barrier) later
+    // and leaves out the last barrier, so every wavefront meets the same
+    // number of barriers.
+    if (grp == 1) phase_barrier();         // phase 0: X reads, Y has nothing to do yet
+    for (int k = 0; k < KT; k++) {
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            reading_phase(k, h);           // X: phase 4k + 2h,     Y: 4k + 2h + 1
+            phase_barrier();
+            multiply();                    // X: phase 4k + 2h + 1, Y: 4k + 2h + 2
+            if (grp == 0 || h == 0 || k + 1 < KT) phase_barrier();
+        }
+    }
+
+    // ---- accumulators -> C -----------------------------------------------------
+    {
+        // Everything the addresses and bounds are made of is re-derived here
+        // (opaque to common-subexpression elimination), so that no per-row
+        // address or lane mask of the C load is kept alive across the k loop.
+        int Mb = p.M, Nb = p.N, lane2 = lane, row2 = crow0, col2 = ccol0;
+        int64_t ldc2 = p.ldc;
+        CT* C2 = Cbase;
+        asm volatile("" : "+s"(Mb), "+s"(Nb), "+s"(row2), "+s"(col2), "+s"(ldc2), "+s"(C2), "+v"(lane2));
+        store_c_tile<CT, 4, 2>(acc, C2, ldc2, row2, col2, lane2, Mb, Nb, edge);
+    }
+}
+
+int64_t grid_pp256(int64_t M, int64_t N)
+{
+    const int64_t tm = (M + PBM - 1) / PBM, tn = (N + PBN - 1) / PBN;
+    if (tm > 0 && tn > INT32_MAX / tm) return -1;
+    return tm * tn;
+}
+
+int launch_pp256(const GemmArgs& a)
+{
+    const int64_t g = grid_pp256(a.M, a.N);
+    if (g < 0) return GEMM_F16_ERR_SIZE;
+    TiledParams p;
+    p.M = (int)a.M; p.N = (int)a.N; p.K = (int)a.K;
+    p.A = a.A; p.lda = a.lda; p.B = a.B; p.ldb = a.ldb; p.C = a.C; p.ldc = a.ldc;
+    p.tiles_m = (int)((a.M + PBM - 1) / PBM);
+    p.tiles_n = (int)((a.N + PBN - 1) / PBN);
+    p.group_m = 8 < p.tiles_m ? 8 : p.tiles_m;     // an XCD's 32 concurrent tiles form an 8 x 4 block of C
+    if (a.c_is_f16)
+        hipLaunchKernelGGL(gemm_pp256_kernel<half_t>, dim3((unsigned)g), dim3(512), 0, a.stream, p);
+    else
+        hipLaunchKernelGGL(gemm_pp256_kernel<float>, dim3((unsigned)g), dim3(512), 0, a.stream, p);
+    return hipGetLastError() == hipSuccess ? GEMM_F16_OK : GEMM_F16_ERR_LAUNCH;
+}
+
+const GemmConfigDesc kPingPong = {
+    "pp256x256x64_w2x4", PBM, PBN, BK, 8, 128, 64, PP_LDS, true, launch_pp256, grid_pp256};
+
+}  // namespace
+
+const GemmConfigDesc* pingpong_config() { return &kPingPong; }

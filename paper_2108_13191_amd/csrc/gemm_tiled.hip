@@ -26,60 +26,12 @@
 // aligned, lda, ldb, K and N multiples of 8.  M is arbitrary.  Rows beyond M
 // and columns beyond N are fetched from clamped (valid) addresses and never
 // stored; the k tail (K % 64) is zero-filled through registers.
-#include "gemm_common.h"
+#include "gemm_device.h"
 #include "../../include/gemm_f16.h"
 
 namespace {
 
-constexpr int BK = 64;             // k extent per LDS stage (f16 elements)
-constexpr int NUM_XCD = 8;
-
-struct TiledParams {
-    int M, N, K;
-    const half_t* A; int64_t lda;
-    const half_t* B; int64_t ldb;
-    void* C; int64_t ldc;
-    int tiles_m, tiles_n, group_m;
-};
-
-typedef __attribute__((address_space(3))) void* lds_ptr_t;
-typedef __attribute__((address_space(1))) const void* gbl_ptr_t;
-typedef __attribute__((address_space(3))) shortx4* lds_s4_ptr_t;
-
-__device__ __forceinline__ void async_copy16(const void* g, uint32_t lds_byte_addr)
-{
-    // 16 bytes per lane, global -> LDS at (uniform) lds_byte_addr + 16 * lane
-    __builtin_amdgcn_global_load_lds((gbl_ptr_t)g, (lds_ptr_t)(uintptr_t)lds_byte_addr, 16, 0, 0);
-}
-
-__device__ __forceinline__ half8 lds_read_b128(uint32_t addr)
-{
-    return *(__attribute__((address_space(3))) const half8*)(uintptr_t)addr;
-}
-
-__device__ __forceinline__ half4 lds_read_tr16(uint32_t addr)
-{
-    shortx4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr_t)(uintptr_t)addr);
-    return __builtin_bit_cast(half4, v);
-}
-
-// Workgroup id -> C tile.  Ids are dealt to the XCDs round-robin; give XCD x
-// the x-th contiguous slice of a tile order that walks group_m tile rows at a
-// time, column by column.
-__device__ __forceinline__ void tile_of_block(const TiledParams& p, int pid, int& tile_m, int& tile_n)
-{
-    const int num = p.tiles_m * p.tiles_n;
-    const int q = num / NUM_XCD, r = num % NUM_XCD;
-    const int x = pid % NUM_XCD;
-    const int l = x * q + (x < r ? x : r) + pid / NUM_XCD;
-    const int group_size = p.group_m * p.tiles_n;
-    const int g = l / group_size;
-    const int first_m = g * p.group_m;
-    const int gm = (p.tiles_m - first_m < p.group_m) ? (p.tiles_m - first_m) : p.group_m;
-    const int in_group = l % group_size;
-    tile_m = first_m + in_group % gm;
-    tile_n = in_group / gm;
-}
+using namespace gemm_dev;
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, typename CT>
 __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_tiled_kernel(const TiledParams p)
@@ -117,22 +69,27 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_tiled_kernel(cons
     // A: copy q covers tile rows 8q .. 8q+7 (128 bytes each); lane i writes LDS
     // chunk (row 8q + i/8, position i%8), which must hold logical chunk
     // position ^ ((row/2)%8).
-    const half_t* a_src[NTA];
+    // Global addresses are a wave-uniform 64-bit base (tile origin, advanced by
+    // one k step per iteration) plus a per-lane 32-bit byte offset that never
+    // changes.
+    const half_t* const a_tile = p.A + (int64_t)m0 * p.lda;
+    const half_t* const b_tile = p.B + n0;
+    uint32_t a_off[NTA];
     int a_chunk;                                  // logical 16-byte chunk (8 k) this lane fetches
     {
         const int sw = 4 * (wave & 1) + (lane >> 4);              // (row/2)%8 for row = 8q + lane/8, q = wave mod 2
         a_chunk = (lane & 7) ^ sw;
 #pragma unroll
         for (int t = 0; t < NTA; t++) {
-            int row = m0 + 8 * (wave + NW * t) + (lane >> 3);
-            row = row < p.M ? row : p.M - 1;                        // clamp: loaded, never stored
-            a_src[t] = p.A + (int64_t)row * p.lda + 8 * a_chunk;
+            int row = 8 * (wave + NW * t) + (lane >> 3);
+            row = (m0 + row < p.M) ? row : p.M - 1 - m0;            // clamp: loaded, never stored
+            a_off[t] = ((uint32_t)row * (uint32_t)p.lda + 8 * a_chunk) * 2;
         }
     }
     // B: copy q covers k rows B_RPI*q .. ; lane i writes (row B_RPI*q + i/B_LPR,
     // chunk position i%B_LPR), which must hold the logical chunk whose 64-byte
     // granule index is XORed with row%4 (two granules per row: with (row/2)%2).
-    const half_t* b_src[NTB];
+    uint32_t b_off[NTB];
     int b_krow[NTB];
     {
         const int pos = lane % B_LPR;
@@ -141,10 +98,10 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_tiled_kernel(cons
             const int krow = B_RPI * (wave + NW * t) + lane / B_LPR;
             const int sw = (B_ROW >= 256) ? (krow & 3) : ((krow >> 1) & 1);
             const int chunk = pos ^ (sw << 2);
-            int col = n0 + 8 * chunk;
-            col = (col + 8 <= p.N) ? col : n0;                      // clamp: loaded, never stored
+            int col = 8 * chunk;
+            col = (n0 + col + 8 <= p.N) ? col : 0;                  // clamp: loaded, never stored
             b_krow[t] = krow;
-            b_src[t] = p.B + (int64_t)krow * p.ldb + col;
+            b_off[t] = ((uint32_t)krow * (uint32_t)p.ldb + col) * 2;
         }
     }
 
@@ -154,10 +111,10 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_tiled_kernel(cons
         const int64_t k0 = (int64_t)kt * BK;
 #pragma unroll
         for (int t = 0; t < NTA; t++)
-            async_copy16(a_src[t] + k0, a_dst + 1024 * (wave + NW * t));
+            async_copy16(a_tile + k0, a_off[t], a_dst + 1024 * (wave + NW * t));
 #pragma unroll
         for (int t = 0; t < NTB; t++)
-            async_copy16(b_src[t] + k0 * p.ldb, b_dst + 1024 * (wave + NW * t));
+            async_copy16(b_tile + k0 * p.ldb, b_off[t], b_dst + 1024 * (wave + NW * t));
     };
     // k tail: same LDS placement, through registers, zero where k >= K
     auto issue_stage_tail = [&](int kt, int buf) {
@@ -169,13 +126,13 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_tiled_kernel(cons
 #pragma unroll
         for (int t = 0; t < NTA; t++) {
             uintx4 v = zero;
-            if (8 * a_chunk < kvalid) v = *reinterpret_cast<const uintx4*>(a_src[t] + k0);
+            if (8 * a_chunk < kvalid) v = *reinterpret_cast<const uintx4*>((const char*)(a_tile + k0) + a_off[t]);
             *(__attribute__((address_space(3))) uintx4*)(uintptr_t)(a_dst + 1024 * (wave + NW * t) + 16 * lane) = v;
         }
 #pragma unroll
         for (int t = 0; t < NTB; t++) {
             uintx4 v = zero;
-            if (b_krow[t] < kvalid) v = *reinterpret_cast<const uintx4*>(b_src[t] + k0 * p.ldb);
+            if (b_krow[t] < kvalid) v = *reinterpret_cast<const uintx4*>((const char*)(b_tile + k0 * p.ldb) + b_off[t]);
             *(__attribute__((address_space(3))) uintx4*)(uintptr_t)(b_dst + 1024 * (wave + NW * t) + 16 * lane) = v;
         }
     };
