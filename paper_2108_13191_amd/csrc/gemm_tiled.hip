@@ -105,154 +105,155 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_tiled_kernel(cons
         }
     }
 
-    auto issue_stage_async = [&](int kt, int buf) {
-        const uint32_t a_dst = smem_base + buf * STAGE;
-        const uint32_t b_dst = a_dst + A_STAGE;
-        const int64_t k0 = (int64_t)kt * BK;
-#pragma unroll
-        for (int t = 0; t < NTA; t++)
-            async_copy16(a_tile + k0, a_off[t], a_dst + 1024 * (wave + NW * t));
-#pragma unroll
-        for (int t = 0; t < NTB; t++)
-            async_copy16(b_tile + k0 * p.ldb, b_off[t], b_dst + 1024 * (wave + NW * t));
-    };
-    // k tail: same LDS placement, through registers, zero where k >= K
-    auto issue_stage_tail = [&](int kt, int buf) {
-        const uint32_t a_dst = smem_base + buf * STAGE;
-        const uint32_t b_dst = a_dst + A_STAGE;
-        const int64_t k0 = (int64_t)kt * BK;
-        const int kvalid = p.K - (int)k0;                           // 8 .. 56, multiple of 8
-        const uintx4 zero = {0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int t = 0; t < NTA; t++) {
-            uintx4 v = zero;
-            if (8 * a_chunk < kvalid) v = *reinterpret_cast<const uintx4*>((const char*)(a_tile + k0) + a_off[t]);
-            *(__attribute__((address_space(3))) uintx4*)(uintptr_t)(a_dst + 1024 * (wave + NW * t) + 16 * lane) = v;
-        }
-#pragma unroll
-        for (int t = 0; t < NTB; t++) {
-            uintx4 v = zero;
-            if (b_krow[t] < kvalid) v = *reinterpret_cast<const uintx4*>((const char*)(b_tile + k0 * p.ldb) + b_off[t]);
-            *(__attribute__((address_space(3))) uintx4*)(uintptr_t)(b_dst + 1024 * (wave + NW * t) + 16 * lane) = v;
-        }
-    };
-
     const int kt_full = p.K / BK;
-    const int kt_total = (p.K + BK - 1) / BK;
-    auto issue_stage = [&](int kt, int buf) {
-        if (kt < kt_full) issue_stage_async(kt, buf); else issue_stage_tail(kt, buf);
+    const int KT = (p.K + BK - 1) / BK;
+
+    // copy number idx (0 .. NTA+NTB-1) of this wavefront for k step kt into LDS
+    // stage `buf`; the k tail goes through registers and is zero beyond K
+    constexpr int NC = NTA + NTB;
+    auto issue_copy = [&](int kt, int buf, int idx) {
+        const uint32_t a_dst = smem_base + buf * STAGE;
+        const uint32_t b_dst = a_dst + A_STAGE;
+        const int64_t k0 = (int64_t)kt * BK;
+        const bool is_a = idx < NTA;
+        const int t = is_a ? idx : idx - NTA;
+        const char* src = is_a ? (const char*)(a_tile + k0) : (const char*)(b_tile + k0 * p.ldb);
+        const uint32_t off = is_a ? a_off[is_a ? t : 0] : b_off[is_a ? 0 : t];
+        const uint32_t dst = (is_a ? a_dst : b_dst) + 1024 * (wave + NW * t);
+        if (kt < kt_full) {
+            async_copy16(src, off, dst);
+        } else {
+            const int kvalid = p.K - (int)k0;                       // 8 .. 56, multiple of 8
+            uintx4 v = {0u, 0u, 0u, 0u};
+            const bool ok = is_a ? (8 * a_chunk < kvalid) : (b_krow[is_a ? 0 : t] < kvalid);
+            if (ok) v = *reinterpret_cast<const uintx4*>(src + off);
+            *(__attribute__((address_space(3))) uintx4*)(uintptr_t)(dst + 16 * lane) = v;
+        }
     };
 
-    if (kt_total > 0) issue_stage(0, 0);
+    // ---- prologue: the first two k steps' copies, then the C tile ------------
+#pragma unroll
+    for (int i = 0; i < NC; i++) issue_copy(0, 0, i);
+    if (KT > 1) {
+#pragma unroll
+        for (int i = 0; i < NC; i++) issue_copy(1, 1, i);
+    }
 
-    // ---- C tile -> accumulators ---------------------------------------------
     // accumulator register i of lane l: row 8*(i/4) + 4*(l/32) + i%4, column l%32
     floatx16 acc[FM][FN];
     CT* const Cbase = (CT*)p.C;
-    const int crow0 = m0 + wm_base + 4 * (lane >> 5);
-    const int ccol0 = n0 + wn_base + (lane & 31);
-    if (!edge) {
-#pragma unroll
-        for (int fm = 0; fm < FM; fm++)
-#pragma unroll
-            for (int fn = 0; fn < FN; fn++)
-#pragma unroll
-                for (int i = 0; i < 16; i++) {
-                    const int row = crow0 + fm * 32 + 8 * (i / 4) + (i & 3);
-                    acc[fm][fn][i] = (float)Cbase[(int64_t)row * p.ldc + ccol0 + fn * 32];
-                }
-    } else {
-#pragma unroll
-        for (int fm = 0; fm < FM; fm++)
-#pragma unroll
-            for (int fn = 0; fn < FN; fn++)
-#pragma unroll
-                for (int i = 0; i < 16; i++) {
-                    const int row = crow0 + fm * 32 + 8 * (i / 4) + (i & 3);
-                    const int col = ccol0 + fn * 32;
-                    float v = 0.0f;
-                    if (row < p.M && col < p.N) v = (float)Cbase[(int64_t)row * p.ldc + col];
-                    acc[fm][fn][i] = v;
-                }
-    }
+    load_c_tile<CT, FM, FN>(acc, Cbase, p.ldc, m0 + wm_base, n0 + wn_base, lane, p.M, p.N, edge);
 
     // ---- fragment read addresses (per lane, constant over k) -----------------
     // A operand of the 32x32x16 MFMA: lane l holds row l%32, k = 8*(l/32) .. +7
     // of the 16-wide k slice -> logical chunk 2*ks + l/32 of tile row r,
     // stored at position chunk ^ ((r/2)%8).
-    const uint32_t a_row_off = (uint32_t)(wm_base + (lane & 31)) * (BK * 2);
-    const int a_sw = (lane >> 1) & 7;
+    uint32_t a_rd[BK / 16];
+    {
+        const uint32_t row_off = (uint32_t)(wm_base + (lane & 31)) * (BK * 2);
+        const int sw = (lane >> 1) & 7;
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ks++)
+            a_rd[ks] = smem_base + row_off + (uint32_t)(((2 * ks + (lane >> 5)) ^ sw) * 16);
+    }
     // B operand: lane l holds column l%32, the same k.  One transposing read
     // serves 16 lanes: lanes 4r..4r+3 of a 16-lane block point at 16
     // consecutive columns of k row r, and lane i receives column i of rows
     // 0..3.  Blocks 0,1 are the two column halves of k 0..7, blocks 2,3 of
     // k 8..15; two reads (k +0..3, +4..7) make one operand.
-    const int blk = lane >> 4, j = lane & 15;
-    const uint32_t b_lane_off = (uint32_t)(8 * (blk >> 1) + (j >> 2)) * B_ROW
-                              + (uint32_t)(16 * (blk & 1) + 4 * (j & 3)) * 2;
-    const int b_sw = (B_ROW >= 256) ? (j >> 2) : ((j >> 3) & 1);   // swizzle term of this lane's k row
+    uint32_t b_rd[FN];
+    {
+        const int blk = lane >> 4, j = lane & 15;
+        const uint32_t lane_off = (uint32_t)(8 * (blk >> 1) + (j >> 2)) * B_ROW + (uint32_t)(16 * (blk & 1) + 4 * (j & 3)) * 2;
+        const int sw = (B_ROW >= 256) ? (j >> 2) : ((j >> 3) & 1);   // swizzle term of this lane's k row
+#pragma unroll
+        for (int fn = 0; fn < FN; fn++)
+            b_rd[fn] = smem_base + A_STAGE + lane_off + (uint32_t)((((wn_base >> 5) + fn) ^ sw) * 64);
+    }
+
+    // Fragments are double-buffered by 16-wide k slice: while the MFMAs of slice
+    // ks run from fa/fb[ks&1], the reads of slice ks+1 fill fa/fb[(ks+1)&1].
+    half8 fa[2][FM], fb[2][FN];
+    constexpr int NR = FM + 2 * FN;                 // LDS reads per slice: A b128, B 2 x tr_b64
+    half4 b_lo[FN];                                 // first half of a B operand until its second read is issued
+
+    // read number r (0 .. NR-1) of slice ks of LDS stage `buf` into fragment set d:
+    // B operands first (every MFMA row needs all of them), then A
+    auto issue_read = [&](uint32_t stage_off, int ks, int d, int r) {
+        if (r < 2 * FN) {
+            const int fn = r >> 1;
+            const uint32_t base = b_rd[fn] + stage_off + ks * 16 * B_ROW;
+            if ((r & 1) == 0) b_lo[fn] = lds_read_tr16(base);
+            else fb[d][fn] = __builtin_shufflevector(b_lo[fn], lds_read_tr16(base + 4 * B_ROW), 0, 1, 2, 3, 4, 5, 6, 7);
+        } else {
+            const int fm = r - 2 * FN;
+            fa[d][fm] = lds_read_b128(a_rd[ks] + stage_off + fm * 32 * (BK * 2));
+        }
+    };
+
+    // prologue copies and the C tile have landed; publish, then fetch slice 0
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int r = 0; r < NR; r++) issue_read(0, 0, 0, r);
 
     // ---- main loop -------------------------------------------------------------
-    for (int kt = 0; kt < kt_total; kt++) {
-        const int buf = kt & 1;
-        // this wave's copies into `buf` have landed; after the barrier so have
-        // everyone's, and everyone is done reading the other buffer
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (kt + 1 < kt_total) issue_stage(kt + 1, buf ^ 1);
-
-        const uint32_t a_lds = smem_base + buf * STAGE;
-        const uint32_t b_lds = a_lds + A_STAGE;
+    // One barrier per k step, placed in front of the last slice: behind it the
+    // stage just consumed is free (copies for k step kt+2 go there, a whole k
+    // step before they are needed) and the next stage is complete (its slice 0
+    // is fetched while the last slice is multiplied).  Every slice is cut into
+    // FM chunks {a share of the next slice's LDS reads, a share of the copies,
+    // one row of MFMAs}; the scheduler may reorder inside a chunk only, so LDS
+    // and copy instructions are issued in the shadow of the MFMAs around them.
+    for (int kt = 0; kt < KT; kt++) {
+        const uint32_t cur = (uint32_t)(kt & 1) * STAGE, nxt = cur ^ STAGE;
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ks++) {
-            half8 a[FM], b[FN];
+        for (int ks = 0; ks < BK / 16 - 1; ks++) {
 #pragma unroll
-            for (int fm = 0; fm < FM; fm++) {
-                const uint32_t chunk = (uint32_t)((2 * ks + (lane >> 5)) ^ a_sw);
-                a[fm] = lds_read_b128(a_lds + a_row_off + fm * 32 * (BK * 2) + chunk * 16);
-            }
+            for (int c = 0; c < FM; c++) {
 #pragma unroll
-            for (int fn = 0; fn < FN; fn++) {
-                const int g = (wn_base >> 5) + fn;                  // 64-byte granule of this fragment's columns
-                const uint32_t goff = (uint32_t)(g ^ b_sw) * 64;
-                const uint32_t base = b_lds + b_lane_off + goff + ks * 16 * B_ROW;
-                const half4 lo = lds_read_tr16(base);
-                const half4 hi = lds_read_tr16(base + 4 * B_ROW);
-                b[fn] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            }
-#pragma unroll
-            for (int fm = 0; fm < FM; fm++)
+                for (int r = c * NR / FM; r < (c + 1) * NR / FM; r++) issue_read(cur, ks + 1, (ks + 1) & 1, r);
 #pragma unroll
                 for (int fn = 0; fn < FN; fn++)
-                    acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[fm], b[fn], acc[fm][fn], 0, 0, 0);
+                    acc[c][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ks & 1][c], fb[ks & 1][fn], acc[c][fn], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        // this wave's copies of k step kt+1 have landed and its reads of this
+        // stage are complete; after the barrier that holds for every wave
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        const bool more = kt + 1 < KT, copy = kt + 2 < KT;
+#pragma unroll
+        for (int c = 0; c < FM; c++) {
+            if (more) {
+#pragma unroll
+                for (int r = c * NR / FM; r < (c + 1) * NR / FM; r++) issue_read(nxt, 0, 0, r);
+            }
+            if (copy) {
+#pragma unroll
+                for (int i = c * NC / FM; i < (c + 1) * NC / FM; i++) issue_copy(kt + 2, kt & 1, i);
+            }
+#pragma unroll
+            for (int fn = 0; fn < FN; fn++)
+                acc[c][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[1][c], fb[1][fn], acc[c][fn], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 
     // ---- accumulators -> C -----------------------------------------------------
-    if (!edge) {
-#pragma unroll
-        for (int fm = 0; fm < FM; fm++)
-#pragma unroll
-            for (int fn = 0; fn < FN; fn++)
-#pragma unroll
-                for (int i = 0; i < 16; i++) {
-                    const int row = crow0 + fm * 32 + 8 * (i / 4) + (i & 3);
-                    Cbase[(int64_t)row * p.ldc + ccol0 + fn * 32] = (CT)acc[fm][fn][i];   // f16: one rounding, to nearest even
-                }
-    } else {
-        // bounds re-derived here (not carried across the k loop as lane masks)
-        int Mb = p.M, Nb = p.N;
-        asm volatile("" : "+s"(Mb), "+s"(Nb));
-#pragma unroll
-        for (int fm = 0; fm < FM; fm++)
-#pragma unroll
-            for (int fn = 0; fn < FN; fn++)
-#pragma unroll
-                for (int i = 0; i < 16; i++) {
-                    const int row = crow0 + fm * 32 + 8 * (i / 4) + (i & 3);
-                    const int col = ccol0 + fn * 32;
-                    if (row < Mb && col < Nb) Cbase[(int64_t)row * p.ldc + col] = (CT)acc[fm][fn][i];
-                }
+    {
+        // Everything the addresses and bounds are made of is re-derived here
+        // (opaque to common-subexpression elimination), so that no per-row
+        // address or lane mask of the C load is kept alive across the k loop.
+        int Mb = p.M, Nb = p.N, lane2 = lane, row2 = m0 + wm_base, col2 = n0 + wn_base;
+        int64_t ldc2 = p.ldc;
+        CT* C2 = Cbase;
+        asm volatile("" : "+s"(Mb), "+s"(Nb), "+s"(row2), "+s"(col2), "+s"(ldc2), "+s"(C2), "+v"(lane2));
+        store_c_tile<CT, FM, FN>(acc, C2, ldc2, row2, col2, lane2, Mb, Nb, edge);
     }
 }
 
