@@ -44,3 +44,6 @@ const GemmConfigDesc* tiled_config(int i);
 
 // gemm_pingpong.hip
 const GemmConfigDesc* pingpong_config();
+
+// gemm_w4.hip
+const GemmConfigDesc* w4_config();
