@@ -240,6 +240,13 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     // ago (only the 8 issued since may be outstanding) and (b) the fragment
     // reads, so that the barrier that follows publishes both.
     auto reading_phase = [&](int k, int h) {
+        // LDS reads first: they issue in a few cycles each and complete on their
+        // own.  The copies behind them are paced by the texture addresser (a
+        // wave-wide 1 KB copy occupies it for 16 cycles and the four reading
+        // wavefronts issue theirs together), so they would hold up every
+        // instruction placed after them.
+        read_fragments(k, h);
+        __builtin_amdgcn_sched_barrier(0);
         if (grp == 0) {
             if (h == 0) { if (k + 1 < KT) copy_a_half(k + 1, 1, a_off); }
             else        { if (k + 2 < KT) copy_b_half(k + 2, 0, b_off); }
@@ -247,7 +254,6 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
             if (h == 0) { if (k + 2 < KT) copy_b_half(k + 2, 1, b_off); }
             else        { if (k + 2 < KT) copy_a_half(k + 2, 0, a_off); }
         }
-        read_fragments(k, h);
         if (k + 2 < kt_full) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
         else                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");

@@ -1,40 +1,46 @@
 // The large-problem kernel: 256 x 256 C tile per workgroup, FOUR wavefronts
-// (one per SIMD), each owning a 128 x 128 block: 16 accumulators of 32 x 32 =
-// 256 registers, the whole AccVGPR file.  k steps of 64, f16 MFMA
-// (v_mfma_f32_32x32x16_f16), f32 accumulation.
+// (one per SIMD), each owning a 128 x 128 block: 8 x 8 accumulators of 16 x 16
+// = 256 registers, the whole AccVGPR file.  k steps of 64, f16 MFMA
+// (v_mfma_f32_16x16x32_f16), f32 accumulation.
 //
-// Why this shape on MI355X: under a dense MFMA load the part is power-bound,
-// so what counts is work per flop.  A 128 x 128 wavefront tile reads
-// (128 + 128) x 64 f16 = 32 KB of LDS per k step and wavefront, 128 KB per
-// workgroup, one third less than eight wavefronts of 128 x 64; and each LDS
-// byte is fetched from L2 once per 256 x 256 tile.
+// Why this shape on MI355X: under a dense MFMA load with random operands the
+// part is power-bound (an MFMA-only loop on N(0,1) data sustains about 64 % of
+// the nominal rate), so what counts is energy per flop.  A 128 x 128 wavefront
+// tile reads (128 + 128) x 64 f16 = 32 KB of LDS per k step and wavefront, one
+// third less than eight wavefronts of 128 x 64; the 16x16x32 instruction moves
+// fewer accumulator bytes per flop than 32x32x16 and measured 6 % faster in
+// that MFMA-only loop.
 //
 // The steps are those of the paper's recipe (Algorithm "Two-level tiled tensor
-// core Matmul"; C hoisted out of the k loop, section "Generating WMMA Ops and
-// More"; the copies of later k tiles in flight while the current one is
-// multiplied, sections "Global Memory Load Latency Hiding" and "Completing
-// Latency Hiding"), re-timed for one wavefront per SIMD:
+// core Matmul"; C handled once per tile outside the k loop, section
+// "Generating WMMA Ops and More"; the copies of later k tiles in flight while
+// the current one is multiplied, sections "Global Memory Load Latency Hiding"
+// and "Completing Latency Hiding"), re-timed for one wavefront per SIMD:
 //
-//   * A k step is 64 MFMAs per wavefront, cut into 16 chunks of 4 MFMAs (one
-//     accumulator row of one 16-wide k slice).  Every chunk also carries 3 of
-//     the 12 LDS fragment reads of the NEXT slice (fragments are double
-//     buffered in registers) and exactly ONE global -> LDS copy, so that the
-//     LDS and the texture path see an even load and everything is issued in
-//     the shadow of the MFMAs.  The scheduler may not move anything across a
-//     chunk boundary.
+//   * A k step is two 32-wide k slices of 64 MFMAs per wavefront.  The
+//     wavefront is alone on its SIMD and issues in order, so an instruction
+//     placed behind an MFMA that waits for the matrix pipe waits with it;
+//     therefore every pair of MFMAs is followed by exactly one other
+//     instruction -- one of the 24 LDS fragment reads of the NEXT slice
+//     (fragments are double buffered in registers) or one of the 8 global ->
+//     LDS copies of the slice -- which issues in the shadow of the MFMAs.  The
+//     scheduler is told to keep that order.
 //   * LDS (160 KB): 2 A buffers (256 x 64 f16, 32 KB) and 3 B buffers (64 x 256
-//     f16, 32 KB).  One workgroup barrier per k step, in front of the last
-//     slice: behind it the A buffer just consumed takes the copies of k step
-//     +2 (issued over the next 8 chunks, at least 8 chunks before they are
-//     needed) and the B buffer consumed one step earlier takes k step +3's
-//     (issued over the following 8 chunks, more than a k step ahead).
+//     f16, 32 KB).  One workgroup barrier per k step, between the two slices:
+//     behind it the A buffer just consumed takes the copies of k step +2
+//     (issued during the second slice, a whole slice before they are needed)
+//     and the B buffer consumed one step earlier takes k step +2's B during
+//     the following first slice (more than a k step ahead).
 //   * Copies are global_load_lds_dwordx4, XOR-swizzled by the choice of the
-//     chunk each lane fetches; A fragments ds_read_b128, B fragments
-//     ds_read_b64_tr_b16.
+//     16-byte chunk each lane fetches; A fragments ds_read_b128, B fragments
+//     ds_read_b64_tr_b16 (B is N-contiguous, the MFMA wants K-contiguous
+//     lanes).
 //   * The MFMA is issued with the B fragment as first operand, i.e. it forms
-//     the transposed 32 x 32 block: a lane then owns 4 CONSECUTIVE columns of
-//     one row of C per register group, so C is loaded and stored 16 bytes per
-//     lane (f32) instead of 4.
+//     the transposed 16 x 16 block: a lane then owns 4 CONSECUTIVE columns of
+//     one row of C, so C moves 16 bytes per lane (f32) instead of 4.
+//   * The accumulators start at zero.  C is read once: a quarter of the tile
+//     during the last k step (whose copy slots are empty), the rest while the
+//     first quarters are added and stored.  C + sum is formed as sum + C.
 //
 // Requirements as for the other tuned kernels: A, B 16-byte aligned; lda, ldb,
 // K, N multiples of 8.  Rows >= M / columns >= N are fetched from clamped
@@ -90,18 +96,20 @@ __global__ __launch_bounds__(256) void gemm_w4_kernel(const TiledParams p)
         row = (m0 + row < p.M) ? row : p.M - 1 - m0;                 // clamp: loaded, never stored
         a_off[t] = ((uint32_t)row * (uint32_t)p.lda + 8 * a_chunk) * 2;
     }
-    // B stage = 32 copies of 2 k rows x 512 B; lane i writes (k row 2q + i/32,
-    // chunk position i%32), which must hold the chunk whose 64-byte granule
-    // index is XORed with (k row)%4.
+    // B stage = 32 copies of 2 k rows x 512 B; copy q = w + 4t covers k rows 2q,
+    // 2q+1.  Lane i writes (k row 2q + i/32, chunk position i%32), which must
+    // hold logical chunk position ^ swz(k row), swz = 4*(row%4) + 2*((row/8)%2):
+    // the row%4 term spreads the four k rows of one transposing read over the
+    // banks, the (row/8)%2 term those of the two 16-lane blocks (k and k+8)
+    // that are served together.  (row/8)%2 = t%2 here.
     uint32_t b_off[NCOPY];
     const int b_krow0 = 2 * wave + (lane >> 5);                       // k row of copy t: b_krow0 + 8t
-    {
-        const int sw = 2 * (wave & 1) + (lane >> 5);                  // (2q + i/32) % 4
-        int col = 8 * ((lane & 31) ^ (sw << 2));
-        if (n0 + col + 8 > p.N) col = 0;                              // clamp: loaded, never stored
 #pragma unroll
-        for (int t = 0; t < NCOPY; t++)
-            b_off[t] = ((uint32_t)(b_krow0 + 8 * t) * (uint32_t)p.ldb + col) * 2;
+    for (int t = 0; t < NCOPY; t++) {
+        const int swz = ((b_krow0 & 3) << 2) | ((t & 1) << 1);
+        int col = 8 * ((lane & 31) ^ swz);
+        if (n0 + col + 8 > p.N) col = 0;                              // clamp: loaded, never stored
+        b_off[t] = ((uint32_t)(b_krow0 + 8 * t) * (uint32_t)p.ldb + col) * 2;
     }
     // copy t of the A stage of k step s into A buffer s%2
     auto copy_a = [&](int s, int t) {
@@ -131,93 +139,87 @@ __global__ __launch_bounds__(256) void gemm_w4_kernel(const TiledParams p)
     // ---- prologue: what the steady-state schedule does not cover ---------------
 #pragma unroll
     for (int t = 0; t < NCOPY; t++) { copy_a(0, t); copy_b(0, t); }
-    if (KT > 1) {                  // A(1): the first half only, k step 0 issues the second
+    if (KT > 1) {
 #pragma unroll
-        for (int t = 0; t < NCOPY; t++) { if (t < 4) copy_a(1, t); copy_b(1, t); }
+        for (int t = 0; t < NCOPY; t++) { copy_a(1, t); copy_b(1, t); }
     }
 
     // ---- accumulators -------------------------------------------------------
-    // They start at zero; the C tile is read once, during the LAST k step (its
-    // chunks have no copies left to issue), into otherwise idle registers, and
-    // added when the products are complete: C + sum = sum + C.
-    floatx16 acc[4][4];
+    floatx4 acc[8][8];
 #pragma unroll
-    for (int fm = 0; fm < 4; fm++)
+    for (int fm = 0; fm < 8; fm++)
 #pragma unroll
-        for (int fn = 0; fn < 4; fn++)
-#pragma unroll
-            for (int i = 0; i < 16; i++) acc[fm][fn][i] = 0.0f;
+        for (int fn = 0; fn < 8; fn++) acc[fm][fn] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
     CT* const Cbase = (CT*)p.C;
     typedef typename CVec4<CT>::type ctx4;
-    // Transposed 32 x 32 blocks (B fragment first): register i of lane l is row
-    // l%32, column 8*(i/4) + 4*(l/32) + i%4 -- group g = i/4 is 4 consecutive
-    // columns of one row of C: one vector access per (fm, fn, g).
-    const int c_lrow = lane & 31, c_lcol = 4 * (lane >> 5);
+    // Transposed 16 x 16 blocks (B fragment first): register r of lane l is row
+    // l%16, column 4*(l/16) + r of block (fm, fn): one vector access per block.
+    const int c_lrow = lane & 15, c_lcol = 4 * (lane >> 4);
     const uint32_t c_voff = ((uint32_t)c_lrow * (uint32_t)p.ldc + (uint32_t)c_lcol) * (uint32_t)sizeof(CT);
     const int c_row0 = m0 + wm_base, c_col0 = n0 + wn_base;
-    // group (fm, fn, g) lies inside C?  (N is a multiple of 8: all or nothing)
-    auto c_ok = [&](int fm, int fn, int g) -> bool {
-        return !edge || ((c_row0 + fm * 32 + c_lrow < p.M) && (c_col0 + fn * 32 + 8 * g + c_lcol < p.N));
+    // block (fm, fn): is this lane's group inside C?  (N is a multiple of 8: all 4 columns or none)
+    auto c_ok = [&](int fm, int fn) -> bool {
+        return !edge || ((c_row0 + fm * 16 + c_lrow < p.M) && (c_col0 + fn * 16 + c_lcol < p.N));
     };
-    // a group outside C reads the wavefront tile's first group instead (valid)
-    auto c_load = [&](int fm, int fn, int g) -> ctx4 {
+    // a group outside C reads the wavefront tile's first group instead (valid) and is not used
+    auto c_load = [&](int fm, int fn) -> ctx4 {
         const char* base = reinterpret_cast<const char*>(Cbase + (int64_t)c_row0 * p.ldc + c_col0);
-        const bool ok = c_ok(fm, fn, g);
-        const char* rowp = base + (ok ? (int64_t)fm * 32 * p.ldc * (int64_t)sizeof(CT) : 0);
-        const uint32_t off = ok ? c_voff + (uint32_t)((fn * 32 + 8 * g) * sizeof(CT)) : 0u;
+        const bool ok = c_ok(fm, fn);
+        const char* rowp = base + (ok ? (int64_t)fm * 16 * p.ldc * (int64_t)sizeof(CT) : 0);
+        const uint32_t off = ok ? c_voff + (uint32_t)(fn * 16 * sizeof(CT)) : 0u;
         return *reinterpret_cast<const ctx4*>(rowp + off);
     };
-    ctx4 c_lo[2][4][4];            // C of accumulator rows 0, 1: fetched during the last k step
+    ctx4 c_q0[2][8];               // C of accumulator rows 0, 1: fetched during the last k step
 
     // ---- fragment read addresses ----------------------------------------------
-    // A operand: lane l holds tile row (l%32) of its 32-row block, k = 8*(l/32)..+7
-    // of slice ks -> logical chunk 2*ks + l/32, stored at chunk ^ ((row/2)%8).
-    uint32_t a_rd[4];
+    // A operand of the 16x16x32 MFMA: lane l holds tile row l%16 of its 16-row
+    // block, k = 8*(l/16)..+7 of the 32-wide slice s -> logical chunk 4s + l/16,
+    // stored at chunk ^ ((row/2)%8).
+    uint32_t a_rd[2];
     {
-        const uint32_t row_off = (uint32_t)(wm_base + (lane & 31)) * (BK * 2);
-        const int sw = (lane >> 1) & 7;
+        const uint32_t row_off = (uint32_t)(wm_base + (lane & 15)) * (BK * 2);
+        const int sw = (lane & 15) >> 1;
 #pragma unroll
-        for (int ks = 0; ks < 4; ks++)
-            a_rd[ks] = smem_base + row_off + (uint32_t)(((2 * ks + (lane >> 5)) ^ sw) * 16);
+        for (int s = 0; s < 2; s++)
+            a_rd[s] = smem_base + row_off + (uint32_t)(((4 * s + (lane >> 4)) ^ sw) * 16);
     }
-    // B operand: one transposing read serves 16 lanes -- lanes 4r..4r+3 of a
-    // 16-lane block point at 16 consecutive columns of k row r and lane i gets
-    // column i of rows 0..3.  Blocks 0,1: the two column halves at k 0..7,
-    // blocks 2,3: at k 8..15; two reads (k +0..3, +4..7) make one operand.
-    uint32_t b_rd[4];
+    // B operand: lane l holds column l%16, the same k.  One transposing read
+    // serves 16 lanes: lanes 4r..4r+3 of a 16-lane block point at 16
+    // consecutive columns of k row r and lane i receives column i of rows 0..3.
+    // Block b covers k 8b..8b+7 of the slice in two reads (+0..3, +4..7).
+    uint32_t b_rd[8];
     {
         const int blk = lane >> 4, j = lane & 15;
-        const uint32_t lane_off = (uint32_t)(8 * (blk >> 1) + (j >> 2)) * B_ROW + (uint32_t)(16 * (blk & 1) + 4 * (j & 3)) * 2;
+        const uint32_t row_off = (uint32_t)(8 * blk + (j >> 2)) * B_ROW;
+        const int swz = ((j >> 2) << 2) | ((blk & 1) << 1);           // of k rows 8b + j/4 (+4, +32)
 #pragma unroll
-        for (int fn = 0; fn < 4; fn++)
-            b_rd[fn] = smem_base + B_REGION + lane_off + (uint32_t)((((wn_base >> 5) + fn) ^ (j >> 2)) * 64);
+        for (int fn = 0; fn < 8; fn++) {
+            const int chunk = 2 * ((wn_base >> 4) + fn) + ((j & 3) >> 1);   // 16-byte chunk of columns 4(j%4)..+3
+            b_rd[fn] = smem_base + B_REGION + row_off + (uint32_t)((chunk ^ swz) * 16 + 8 * (j & 1));
+        }
     }
 
-    half8 fa[2][4], fb[2][4];      // fragments of two k slices: [slice & 1][fm], [slice & 1][fn]
-    half4 b_lo[4];                 // first half of a B operand until its second read is issued
+    half8 fa[2][8], fb[2][8];      // fragments of two k slices: [slice & 1][fm], [slice & 1][fn]
+    half4 b_lo[8];                 // first half of a B operand until its second read is issued
 
-    // read r (0..11) of slice ks of (A buffer at a_base, B buffer at b_base)
-    // into fragment set d: B operands first, then A
-    auto issue_read = [&](uint32_t a_base, uint32_t b_base, int ks, int d, int r) {
-        if (r < 8) {
+    // read r (0..23) of slice s of (A buffer at a_base, B buffer at b_base)
+    // into fragment set d: the 8 B operands (2 reads each) first, then the 8 A
+    auto issue_read = [&](uint32_t a_base, uint32_t b_base, int s, int d, int r) {
+        if (r < 16) {
             const int fn = r >> 1;
-            const uint32_t addr = b_rd[fn] + b_base + ks * 16 * B_ROW;
+            const uint32_t addr = b_rd[fn] + b_base + s * 32 * B_ROW;
             if ((r & 1) == 0) b_lo[fn] = lds_read_tr16(addr);
             else fb[d][fn] = __builtin_shufflevector(b_lo[fn], lds_read_tr16(addr + 4 * B_ROW), 0, 1, 2, 3, 4, 5, 6, 7);
         } else {
-            const int fm = r - 8;
-            fa[d][fm] = lds_read_b128(a_rd[ks] + a_base + fm * 32 * (BK * 2));
+            const int fm = r - 16;
+            fa[d][fm] = lds_read_b128(a_rd[s] + a_base + fm * 16 * (BK * 2));
         }
     };
-    // one MFMA; B fragment first = transposed block
-    auto mfma_one = [&](int d, int fm, int fn) {
-        acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[d][fn], fa[d][fm], acc[fm][fn], 0, 0, 0);
+    // MFMA number i (0..63) of a slice, B fragment first = transposed block
+    auto mfma_one = [&](int d, int i) {
+        const int fm = i >> 3, fn = i & 7;
+        acc[fm][fn] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fb[d][fn], fa[d][fm], acc[fm][fn], 0, 0, 0);
     };
-    // The wavefront is alone on its SIMD and issues in order: an instruction
-    // behind an MFMA that waits for the matrix pipe waits with it.  So every
-    // MFMA is followed by exactly one other instruction (an LDS read, a copy, a
-    // C load), which issues in the 32-cycle shadow of that MFMA; the scheduler
-    // is told to keep this order.
     auto fence = [&]() { __builtin_amdgcn_sched_barrier(0); };
 
     // prologue copies have landed; publish, then fetch slice 0
@@ -225,34 +227,25 @@ __global__ __launch_bounds__(256) void gemm_w4_kernel(const TiledParams p)
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 #pragma unroll
-    for (int r = 0; r < 12; r++) issue_read(0, 0, 0, 0, r);
+    for (int r = 0; r < 24; r++) issue_read(0, 0, 0, 0, r);
 
     // ---- main loop -------------------------------------------------------------
-    // Chunk q of k step j: MFMA row q%4 of slice q/4; reads 3(q%4)..+2 of the
-    // next slice; one copy: q 0-3: A(j+1) copies 4-7, q 4-11: B(j+2) copies
-    // 0-7, q 12-15 (behind the barrier): A(j+2) copies 0-3.  The last k step
-    // (LAST) has nothing to copy or prefetch and fetches half of the C tile
-    // instead, 2 vector loads per chunk.
+    // k step j, unit u of a slice = MFMAs 2u, 2u+1 and one companion:
+    //   slice 0: u 0-23 read r = u of slice 1 (same stage); u 24-31 copy B(j+2), copies 0-7
+    //   barrier
+    //   slice 1: u 0-23 read r = u of slice 0 of stage j+1;  u 24-31 copy A(j+2), copies 0-7
+    // The last k step (LAST) has nothing to copy or prefetch; its 16 copy slots
+    // fetch a quarter of the C tile instead.
     auto k_step = [&](int j, auto last_tag) {
         constexpr bool LAST = decltype(last_tag)::value;
         const uint32_t a_cur = (uint32_t)(j & 1) * A_BUF, a_nxt = a_cur ^ A_BUF;
         const uint32_t b_cur = (uint32_t)(j % 3) * B_BUF, b_nxt = (uint32_t)((j + 1) % 3) * B_BUF;
 #pragma unroll
-        for (int q = 0; q < 12; q++) {
-            const int ks = q >> 2, c = q & 3;
-#pragma unroll
-            for (int i = 0; i < 3; i++) {
-                mfma_one(ks & 1, c, i); fence();
-                issue_read(a_cur, b_cur, ks + 1, (ks + 1) & 1, 3 * c + i); fence();
-            }
-            mfma_one(ks & 1, c, 3); fence();
-            if (LAST) {
-#pragma unroll
-                for (int u = 2 * q; u < 2 * q + 2; u++) c_lo[u >> 4][(u >> 2) & 3][u & 3] = c_load(u >> 4, (u >> 2) & 3, u & 3);
-            } else {
-                if (q < 4) copy_a(j + 1, 4 + q);
-                else if (j + 2 < KT) copy_b(j + 2, q - 4);
-            }
+        for (int u = 0; u < 32; u++) {
+            mfma_one(0, 2 * u); mfma_one(0, 2 * u + 1); fence();
+            if (u < 24) issue_read(a_cur, b_cur, 1, 1, u);
+            else if (LAST) c_q0[0][u - 24] = c_load(0, u - 24);
+            else if (j + 2 < KT) copy_b(j + 2, u - 24);
             fence();
         }
         if (LAST) {
@@ -268,19 +261,11 @@ __global__ __launch_bounds__(256) void gemm_w4_kernel(const TiledParams p)
         }
         fence();
 #pragma unroll
-        for (int c = 0; c < 4; c++) {
-#pragma unroll
-            for (int i = 0; i < 3; i++) {
-                mfma_one(1, c, i); fence();
-                if (!LAST) { issue_read(a_nxt, b_nxt, 0, 0, 3 * c + i); fence(); }
-            }
-            mfma_one(1, c, 3); fence();
-            if (LAST) {
-#pragma unroll
-                for (int u = 24 + 2 * c; u < 24 + 2 * c + 2; u++) c_lo[u >> 4][(u >> 2) & 3][u & 3] = c_load(u >> 4, (u >> 2) & 3, u & 3);
-            } else {
-                if (j + 2 < KT) copy_a(j + 2, c);
-            }
+        for (int u = 0; u < 32; u++) {
+            mfma_one(1, 2 * u); mfma_one(1, 2 * u + 1); fence();
+            if (u < 24) { if (!LAST) issue_read(a_nxt, b_nxt, 0, 0, u); }
+            else if (LAST) c_q0[1][u - 24] = c_load(1, u - 24);
+            else if (j + 2 < KT) copy_a(j + 2, u - 24);
             fence();
         }
     };
@@ -288,36 +273,37 @@ __global__ __launch_bounds__(256) void gemm_w4_kernel(const TiledParams p)
     k_step(KT - 1, BoolTag<true>());
 
     // ---- + C, -> C ---------------------------------------------------------------
-    // Rows 2 and 3 of C are fetched while rows 0 and 1 are added and stored (one
-    // row of 64 registers at a time, in the registers the previous row frees).
+    // Quarter by quarter (two accumulator rows = 16 vector accesses per lane):
+    // the next quarter of C is fetched while the current one is added and stored.
     {
-        auto finish_row = [&](int fm, const ctx4 (&cin)[4][4]) {
-            char* rowp = reinterpret_cast<char*>(Cbase + (int64_t)(c_row0 + fm * 32) * p.ldc + c_col0);
+        auto finish_rows = [&](int fm0, const ctx4 (&cin)[2][8]) {
 #pragma unroll
-            for (int fn = 0; fn < 4; fn++)
+            for (int r = 0; r < 2; r++) {
+                const int fm = fm0 + r;
+                char* rowp = reinterpret_cast<char*>(Cbase + (int64_t)(c_row0 + fm * 16) * p.ldc + c_col0);
 #pragma unroll
-                for (int g = 0; g < 4; g++) {
+                for (int fn = 0; fn < 8; fn++) {
                     ctx4 v;
 #pragma unroll
-                    for (int e = 0; e < 4; e++) v[e] = (CT)(acc[fm][fn][4 * g + e] + (float)cin[fn][g][e]);   // f16: one rounding, to nearest even
-                    if (c_ok(fm, fn, g))
-                        *reinterpret_cast<ctx4*>(rowp + c_voff + (fn * 32 + 8 * g) * sizeof(CT)) = v;
+                    for (int e = 0; e < 4; e++) v[e] = (CT)(acc[fm][fn][e] + (float)cin[r][fn][e]);   // f16: one rounding, to nearest even
+                    if (c_ok(fm, fn))
+                        *reinterpret_cast<ctx4*>(rowp + c_voff + fn * 16 * sizeof(CT)) = v;
                 }
+            }
         };
-        ctx4 c_r2[4][4], c_r3[4][4];
+        auto fetch_rows = [&](int fm0, ctx4 (&cin)[2][8]) {
 #pragma unroll
-        for (int u = 0; u < 16; u++) c_r2[u >> 2][u & 3] = c_load(2, u >> 2, u & 3);
-        __builtin_amdgcn_sched_barrier(0);
-        finish_row(0, c_lo[0]);
-        __builtin_amdgcn_sched_barrier(0);
+            for (int r = 0; r < 2; r++)
 #pragma unroll
-        for (int u = 0; u < 16; u++) c_r3[u >> 2][u & 3] = c_load(3, u >> 2, u & 3);
-        __builtin_amdgcn_sched_barrier(0);
-        finish_row(1, c_lo[1]);
-        __builtin_amdgcn_sched_barrier(0);
-        finish_row(2, c_r2);
-        __builtin_amdgcn_sched_barrier(0);
-        finish_row(3, c_r3);
+                for (int fn = 0; fn < 8; fn++) cin[r][fn] = c_load(fm0 + r, fn);
+        };
+        ctx4 c_q1[2][8], c_q2[2][8];
+        fetch_rows(2, c_q1); fetch_rows(4, c_q2); fence();
+        finish_rows(0, c_q0); fence();
+        fetch_rows(6, c_q0); fence();
+        finish_rows(2, c_q1); fence();
+        finish_rows(4, c_q2); fence();
+        finish_rows(6, c_q0);
     }
 }
 
