@@ -37,6 +37,10 @@
 // is visible to everybody at least five phases after it was requested, and a
 // buffer is overwritten only after its last reader has passed a barrier.
 //
+// The accumulators start at zero; C is read once per tile in the epilogue,
+// where the accumulators pass through LDS so that both the read and the write
+// of C are whole row segments, 16 bytes per lane.
+//
 // Requirements as for the other tuned kernels: A, B 16-byte aligned; lda, ldb,
 // K, N multiples of 8.  Rows >= M / columns >= N are fetched from clamped
 // addresses and never stored; the k tail is zero-filled through registers.
@@ -168,13 +172,22 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
         }
     }
 
-    // ---- C tile -> accumulators ---------------------------------------------
-    // accumulator register i of lane l: row 8*(i/4) + 4*(l/32) + i%4, column l%32
+    // ---- accumulators -------------------------------------------------------
+    // They start at zero; C is read once, in the epilogue, and added there
+    // (C + sum formed as sum + C).  The MFMA is issued with the B fragment
+    // first, i.e. it forms the transposed 32 x 32 block: register i of lane l
+    // is row l%32, column 8*(i/4) + 4*(l/32) + i%4 -- 4 consecutive columns per
+    // register group, which the epilogue moves 16 bytes at a time.
     floatx16 acc[4][2];
+#pragma unroll
+    for (int fm = 0; fm < 4; fm++)
+#pragma unroll
+        for (int fn = 0; fn < 2; fn++)
+#pragma unroll
+            for (int i = 0; i < 16; i++) acc[fm][fn][i] = 0.0f;
     CT* const Cbase = (CT*)p.C;
     const int crow0 = m0 + grp * 128;
     const int ccol0 = n0 + wn * 64;
-    load_c_tile<CT, 4, 2>(acc, Cbase, p.ldc, crow0, ccol0, lane, p.M, p.N, edge);
 
     // ---- fragment read addresses ----------------------------------------------
     // A operand: lane l holds tile row (l%32) of its 32-row block, k = 8*(l/32)..+7
@@ -233,7 +246,7 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
             for (int fm = 0; fm < 4; fm++)
 #pragma unroll
                 for (int fn = 0; fn < 2; fn++)
-                    acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[s][fm], fb[s][fn], acc[fm][fn], 0, 0, 0);
+                    acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[s][fn], fa[s][fm], acc[fm][fn], 0, 0, 0);   // B first: transposed block
     };
     // A reading phase for half h of k step k: 4 copies for a later step, the
     // fragment reads, then wait for (a) the copies issued two reading phases
@@ -277,16 +290,54 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
         }
     }
 
-    // ---- accumulators -> C -----------------------------------------------------
+    // ---- + C, -> C ---------------------------------------------------------------
+    // Behind the last barrier nobody reads the A/B buffers any more, so each
+    // wavefront takes 20 KB of LDS as a private transposing buffer: 32 rows x
+    // 64 columns of its accumulators at a time go in as they sit in registers
+    // (16 bytes per lane, row pitch 272 B: conflict-free) and come back with 16
+    // lanes covering one row, so that C is read and written in whole 256-byte
+    // row segments (128 B for f16 C), 16 bytes (8) per lane.
     {
-        // Everything the addresses and bounds are made of is re-derived here
-        // (opaque to common-subexpression elimination), so that no per-row
-        // address or lane mask of the C load is kept alive across the k loop.
-        int Mb = p.M, Nb = p.N, lane2 = lane, row2 = crow0, col2 = ccol0;
-        int64_t ldc2 = p.ldc;
-        CT* C2 = Cbase;
-        asm volatile("" : "+s"(Mb), "+s"(Nb), "+s"(row2), "+s"(col2), "+s"(ldc2), "+s"(C2), "+v"(lane2));
-        store_c_tile<CT, 4, 2>(acc, C2, ldc2, row2, col2, lane2, Mb, Nb, edge);
+        typedef typename CVec4<CT>::type ctx4;
+        constexpr int PITCH = 272;
+        const uint32_t tbuf = smem_base + (uint32_t)wave * 20480u;
+        const uint32_t w_addr = tbuf + (uint32_t)(lane & 31) * PITCH + (uint32_t)(lane >> 5) * 16;
+        const uint32_t r_addr = tbuf + (uint32_t)(lane >> 4) * PITCH + (uint32_t)(lane & 15) * 16;
+        const int orow = lane >> 4, ocol = 4 * (lane & 15);       // this lane's row (of 4) and column in a pass
+        const bool col_ok = !edge || (ccol0 + ocol < p.N);         // N is a multiple of 8: all 4 columns or none
+        CT* const cptr = Cbase + (int64_t)(crow0 + orow) * p.ldc + ccol0 + ocol;
+        ctx4 cin[2][8];
+        auto fetch = [&](int fm, ctx4 (&dst)[8]) {
+#pragma unroll
+            for (int ps = 0; ps < 8; ps++) {
+                const bool ok = col_ok && (!edge || (crow0 + fm * 32 + 4 * ps + orow < p.M));
+                // a group outside C reads this lane's first (valid or clamped) group of the tile instead
+                const CT* src = ok ? cptr + (int64_t)(fm * 32 + 4 * ps) * p.ldc : Cbase + (int64_t)m0 * p.ldc + n0;
+                dst[ps] = *reinterpret_cast<const ctx4*>(src);
+            }
+        };
+        fetch(0, cin[0]);
+#pragma unroll
+        for (int fm = 0; fm < 4; fm++) {
+            if (fm + 1 < 4) fetch(fm + 1, cin[(fm + 1) & 1]);
+#pragma unroll
+            for (int fn = 0; fn < 2; fn++)
+#pragma unroll
+                for (int g = 0; g < 4; g++) {
+                    const floatx4 v = {acc[fm][fn][4 * g], acc[fm][fn][4 * g + 1], acc[fm][fn][4 * g + 2], acc[fm][fn][4 * g + 3]};
+                    *(__attribute__((address_space(3))) floatx4*)(uintptr_t)(w_addr + (fn * 32 + 8 * g) * 4) = v;
+                }
+#pragma unroll
+            for (int ps = 0; ps < 8; ps++) {
+                const floatx4 s4 = *(__attribute__((address_space(3))) const floatx4*)(uintptr_t)(r_addr + 4 * ps * PITCH);
+                const ctx4 c4 = cin[fm & 1][ps];
+                ctx4 o;
+#pragma unroll
+                for (int e = 0; e < 4; e++) o[e] = (CT)(s4[e] + (float)c4[e]);      // f16: one rounding, to nearest even
+                if (col_ok && (!edge || (crow0 + fm * 32 + 4 * ps + orow < p.M)))
+                    *reinterpret_cast<ctx4*>(cptr + (int64_t)(fm * 32 + 4 * ps) * p.ldc) = o;
+            }
+        }
     }
 }
 
