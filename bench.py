@@ -32,6 +32,32 @@ def algorithmic_bytes(M, N, K, c_bytes):
     return 2 * (M * K + K * N) + 2 * M * N * c_bytes
 
 
+def kernel_symbol(tile_name, mode):
+    """Name of the kernel as it shows in a rocprofv3 kernel trace."""
+    ct = "float" if mode == "f32" else "_Float16"
+    if tile_name.startswith("pp256"):
+        return f"gemm_pp256_kernel<{ct}>"
+    if tile_name.startswith("w4_"):
+        return f"gemm_w4_kernel<{ct}>"
+    if tile_name.startswith("generic"):
+        return f"gemm_generic_kernel<{ct}>"
+    return f"gemm_tiled_kernel<{tile_name}, {ct}>"
+
+
+def measured_traffic(tile_name, workload, mode):
+    """HBM bytes per launch (FETCH_SIZE + WRITE_SIZE from rocprofv3 --pmc runs,
+    scaled by a copy kernel of known size) if a committed profile summary under
+    profiles/ records them for this kernel and workload; otherwise None."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{tile_name}_{workload}_{mode}.md")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(float(line.split(":", 1)[1].strip()))
+    except OSError:
+        pass
+    return None
+
+
 def time_gemm(binding, torch, mode, M, N, K, dA, dB, dC, steps, warmup):
     """Return (ms per step over the timed region, list of per-launch ms)."""
     fn = binding.gemm_f16_f32acc if mode == "f32" else binding.gemm_f16_f16acc
@@ -62,7 +88,10 @@ def main():
     ap.add_argument("--workload", default="sq8192_normal")
     ap.add_argument("--mode", default="f32", choices=["f32", "f16"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
-    ap.add_argument("--cpu-rows", type=int, default=768, help="rows of C the oracle is timed on")
+    ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of C the oracle is timed on")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
+                    help="instead of the GEMM, run plain device-to-device copies of this many MiB "
+                         "(calibration of the FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
     ap.add_argument("--sweep", action="store_true", help="also time every workload and the square sweep (extra lines on stderr)")
     ap.add_argument("--force-config", type=int, default=-1)
     args = ap.parse_args()
@@ -75,6 +104,16 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+    if args.copy_probe:
+        n = args.copy_probe << 20
+        src = torch.empty(n, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(args.warmup + args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_read_per_copy": n, "copy_probe_bytes_written_per_copy": n,
+                          "copies": args.warmup + args.steps}))
+        return
     binding.load()
     binding.force_config(args.force_config)
     dev = torch.device("cuda:0")
@@ -107,7 +146,8 @@ def main():
         gbs = r["bytes"] / (avg_launch_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None}
-    roofline.update({"kernel": "gemm_tiled_kernel<" + r["cfg"]["name"] + ">", "avg_launch_ms": round(avg_launch_ms, 5),
+    roofline["traffic"] = measured_traffic(r["cfg"]["name"], args.workload, args.mode)
+    roofline.update({"kernel": kernel_symbol(r["cfg"]["name"], args.mode), "avg_launch_ms": round(avg_launch_ms, 5),
                      "median_launch_ms": round(per[len(per) // 2], 5), "min_launch_ms": round(per[0], 5),
                      "algorithmic_bytes": r["bytes"], "flops": 2 * M * N * K})
 

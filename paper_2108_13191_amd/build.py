@@ -27,6 +27,11 @@ def build(verbose: bool = False, extra=()) -> str:
         raise RuntimeError("hipcc failed")
     if verbose:
         print(resource_table(out))
+    # measurement aid (MFMA-only throughput versus operand data), a stand-alone program
+    probe = os.path.join(HERE, "probe_mfma_ceiling")
+    subprocess.run(["hipcc", "-O3", "--offload-arch=gfx950", "-Wno-unused-command-line-argument",
+                    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                    "-o", probe, os.path.join(CSRC, "probe_mfma_ceiling.hip")], check=True, capture_output=True)
     return LIB
 
 
