@@ -292,7 +292,6 @@ int launch_tiled(const GemmArgs& a)
 
 const GemmConfigDesc kTiled[] = {
     TILED_CONFIG("t256x256x64_w2x4", 256, 256, 2, 4),
-    TILED_CONFIG("t256x256x64_w2x2", 256, 256, 2, 2),
     TILED_CONFIG("t128x128x64_w2x2", 128, 128, 2, 2),
     TILED_CONFIG("t64x64x64_w2x2", 64, 64, 2, 2),
 };
