@@ -8,9 +8,10 @@
 namespace {
 
 // Configuration table: entry 0 is the any-shape kernel, entry 1 the 256 x 256
-// four-wavefront kernel, entry 2 the 256 x 256 phase-alternating eight-wavefront
-// kernel, the rest the generic double-buffered tiles.
-int num_configs() { return 3 + tiled_num_configs(); }
+// four-wavefront kernel, entries 2 and 3 the 256 x 256 phase-alternating
+// eight-wavefront kernel on 32x32x16 and on 16x16x32 MFMAs, the rest the
+// generic double-buffered tiles.
+int num_configs() { return 4 + tiled_num_configs(); }
 
 const GemmConfigDesc kGeneric = {
     "generic64x64x32", 64, 64, 32, 4, 32, 32, 2 * 64 * (32 + 8) * 2,
@@ -18,7 +19,7 @@ const GemmConfigDesc kGeneric = {
 
 const GemmConfigDesc* config(int id)
 {
-    return id == 0 ? &kGeneric : id == 1 ? w4_config() : id == 2 ? pingpong_config() : tiled_config(id - 3);
+    return id == 0 ? &kGeneric : id == 1 ? w4_config() : id == 2 ? pingpong_config() : id == 3 ? pingpong16_config() : tiled_config(id - 4);
 }
 
 int g_forced = -1;
@@ -54,8 +55,8 @@ int select_config(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, c
     if (!aligned_for_tiled(N, K, A, lda, B, ldb)) return 0;
     if (g_forced >= 0 && g_forced < num_configs()) return g_forced;
     struct Cand { int id; double eff; int per_cu; };
-    // ids: 2 = 256x256 (eight wavefronts, phase-alternating), 4 = 128x128, 5 = 64x64
-    const Cand cands[] = {{2, 1.0, 1}, {4, 0.7, 2}, {5, 0.4, 4}};
+    // ids: 2 = 256x256 (eight wavefronts, phase-alternating), 5 = 128x128, 6 = 64x64
+    const Cand cands[] = {{2, 1.0, 1}, {5, 0.7, 2}, {6, 0.4, 4}};
     int best = 2;
     double best_cost = 0;
     for (const Cand& c : cands) {

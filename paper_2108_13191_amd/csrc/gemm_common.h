@@ -44,6 +44,7 @@ const GemmConfigDesc* tiled_config(int i);
 
 // gemm_pingpong.hip
 const GemmConfigDesc* pingpong_config();
+const GemmConfigDesc* pingpong16_config();
 
 // gemm_w4.hip
 const GemmConfigDesc* w4_config();

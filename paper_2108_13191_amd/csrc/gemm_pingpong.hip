@@ -69,7 +69,14 @@ __device__ __forceinline__ void phase_barrier()
     __builtin_amdgcn_sched_barrier(0);
 }
 
-template <typename CT>
+// MI = 32: v_mfma_f32_32x32x16_f16 (4 x 2 accumulators of 32 x 32 per wavefront, two
+// 16-wide k slices per phase); MI = 16: v_mfma_f32_16x16x32_f16 (8 x 4 accumulators
+// of 16 x 16, one 32-wide k slice per phase).  Same LDS image, schedule and epilogue.
+template <int MI> struct AccBlock;
+template <> struct AccBlock<32> { typedef floatx16 type; };
+template <> struct AccBlock<16> { typedef floatx4 type; };
+
+template <typename CT, int MI>
 __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
 {
     __shared__ __attribute__((aligned(1024))) char smem[PP_LDS];
@@ -102,19 +109,18 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
         row = (m0 + row < p.M) ? row : p.M - 1 - m0;                 // clamp: loaded, never stored
         return ((uint32_t)row * (uint32_t)p.lda + 8 * a_chunk) * 2;
     };
-    // B half (32 k rows x 512 B = 16 KB) = 16 copies of 2 k rows; lane i writes
-    // (k row 2q + i/32, chunk position i%32), which must hold the chunk whose
-    // 64-byte granule index is XORed with (k row)%4.
+    // B half (32 k rows x 512 B = 16 KB) = 16 copies of 2 k rows; copy q = wn + 4t.
+    // Lane i writes (k row 2q + i/32, chunk position i%32), which must hold logical
+    // chunk position ^ swz(k row), swz = 4*(row%4) + 2*((row/8)%2): the row%4 term
+    // spreads the four k rows of one transposing read over the banks, the
+    // (row/8)%2 term those of the 16-lane blocks that read k and k+8 together
+    // (16x16x32 operands).  (row/8)%2 = t%2 here.
     const int b_krow_in_copy = lane >> 5;
-    int b_col;
-    {
-        const int sw = 2 * (wn & 1) + (lane >> 5);                   // (2q + i/32) % 4
-        const int chunk = (lane & 31) ^ (sw << 2);
-        b_col = 8 * chunk;
-        if (n0 + b_col + 8 > p.N) b_col = 0;                         // clamp: loaded, never stored
-    }
     auto b_offset = [&](int t) -> uint32_t {                          // relative to the half's first k row
-        return ((uint32_t)(2 * (wn + 4 * t) + b_krow_in_copy) * (uint32_t)p.ldb + b_col) * 2;
+        const int swz = (((2 * wn + b_krow_in_copy) & 3) << 2) | ((t & 1) << 1);
+        int col = 8 * ((lane & 31) ^ swz);
+        if (n0 + col + 8 > p.N) col = 0;                              // clamp: loaded, never stored
+        return ((uint32_t)(2 * (wn + 4 * t) + b_krow_in_copy) * (uint32_t)p.ldb + col) * 2;
     };
 
     // one A half of k step s into A buffer s%2; `off` = the caller's 4 lane offsets
@@ -177,76 +183,90 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     // (C + sum formed as sum + C).  The MFMA is issued with the B fragment
     // first, i.e. it forms the transposed 32 x 32 block: register i of lane l
     // is row l%32, column 8*(i/4) + 4*(l/32) + i%4 -- 4 consecutive columns per
-    // register group, which the epilogue moves 16 bytes at a time.
-    floatx16 acc[4][2];
+    // register group, which the epilogue moves 16 bytes at a time.  (16 x 16
+    // blocks: register r of lane l is row l%16, column 4*(l/16) + r.)
+    constexpr int FM = 128 / MI, FN = 64 / MI;       // accumulator blocks per wavefront tile
+    typedef typename AccBlock<MI>::type acc_t;       // 16 (MI = 32) or 4 (MI = 16) registers
+    acc_t acc[FM][FN];
 #pragma unroll
-    for (int fm = 0; fm < 4; fm++)
+    for (int fm = 0; fm < FM; fm++)
 #pragma unroll
-        for (int fn = 0; fn < 2; fn++)
+        for (int fn = 0; fn < FN; fn++)
 #pragma unroll
-            for (int i = 0; i < 16; i++) acc[fm][fn][i] = 0.0f;
+            for (int i = 0; i < MI * MI / 64; i++) acc[fm][fn][i] = 0.0f;
     CT* const Cbase = (CT*)p.C;
     const int crow0 = m0 + grp * 128;
     const int ccol0 = n0 + wn * 64;
 
     // ---- fragment read addresses ----------------------------------------------
-    // A operand: lane l holds tile row (l%32) of its 32-row block, k = 8*(l/32)..+7
-    // of the 16-wide slice ks -> logical chunk 2*ks + l/32, stored at chunk ^ ((row/2)%8).
-    uint32_t a_rd[4];
+    // MI = 32: A operand lane l holds tile row l%32 of its block, k = 8*(l/32)..+7 of
+    // the 16-wide slice ks -> logical chunk 2*ks + l/32 (4 slices per k step).
+    // MI = 16: row l%16, k = 8*(l/16)..+7 of the 32-wide slice h -> chunk 4*h + l/16
+    // (2 slices per k step).  Either way stored at chunk ^ ((row/2)%8).
+    constexpr int NSL = (MI == 32) ? 4 : 2;          // k slices per k step
+    uint32_t a_rd[NSL];
     {
-        const uint32_t row_off = (uint32_t)(grp * 128 + (lane & 31)) * (BK * 2);
-        const int sw = (lane >> 1) & 7;
+        const int lr = lane & (MI - 1), lk = lane / MI;
+        const uint32_t row_off = (uint32_t)(grp * 128 + lr) * (BK * 2);
+        const int sw = (lr >> 1) & 7;
 #pragma unroll
-        for (int ks = 0; ks < 4; ks++)
-            a_rd[ks] = smem_base + A_REGION + row_off + (uint32_t)(((2 * ks + (lane >> 5)) ^ sw) * 16);
+        for (int sl = 0; sl < NSL; sl++)
+            a_rd[sl] = smem_base + A_REGION + row_off + (uint32_t)((((64 / MI) * sl + lk) ^ sw) * 16);
     }
     // B operand: one transposing read serves 16 lanes -- lanes 4r..4r+3 of a
     // 16-lane block point at 16 consecutive columns of k row r and lane i gets
-    // column i of rows 0..3.  Blocks 0,1: the two column halves at k 0..7,
-    // blocks 2,3: at k 8..15; two reads (k +0..3, +4..7) make one operand.
-    uint32_t b_rd[2];
+    // column i of rows 0..3; two reads (k +0..3, +4..7) make one operand.
+    // MI = 32: blocks 0,1 are the two column halves at k 0..7, blocks 2,3 at k 8..15.
+    // MI = 16: block b covers k 8b..8b+7 of the 32-wide slice.
+    uint32_t b_rd[FN];
     {
         const int blk = lane >> 4, j = lane & 15;
-        const uint32_t lane_off = (uint32_t)(8 * (blk >> 1) + (j >> 2)) * B_ROW + (uint32_t)(16 * (blk & 1) + 4 * (j & 3)) * 2;
+        const int krow = (MI == 32) ? 8 * (blk >> 1) + (j >> 2) : 8 * blk + (j >> 2);   // first read; +4 second
+        const int swz = ((krow & 3) << 2) | (((krow >> 3) & 1) << 1);                    // unchanged by +4, +16, +32
 #pragma unroll
-        for (int fn = 0; fn < 2; fn++)
-            b_rd[fn] = smem_base + B_REGION + lane_off + (uint32_t)(((wn * 2 + fn) ^ (j >> 2)) * 64);
+        for (int fn = 0; fn < FN; fn++) {
+            const int col = wn * 64 + fn * MI + ((MI == 32) ? 16 * (blk & 1) : 0) + 4 * (j & 3);   // first of 4 columns
+            b_rd[fn] = smem_base + B_REGION + (uint32_t)krow * B_ROW + (uint32_t)(((col >> 3) ^ swz) * 16 + 2 * (col & 7));
+        }
     }
 
-    half8 fa[2][4], fb[2][2];      // fragments of half a k step (k slices 2h, 2h+1): [ks][fm], [ks][fn]
+    half8 fa[NSL / 2][FM], fb[NSL / 2][FN];          // fragments of half a k step: [slice][fm], [slice][fn]
 
     auto read_fragments = [&](int k, int h) {
         const uint32_t a_buf = (uint32_t)(k & 1) * A_BUF;
         const uint32_t b_buf = (uint32_t)(k % 3) * B_BUF;
-        // one address register per fragment column (fn) / k slice (ks); the
-        // rest of each address is an instruction offset
-        uint32_t b0[2];
+        // one address register per fragment column (fn) / k slice; the rest of
+        // each address is an instruction offset
+        uint32_t b0[FN];
 #pragma unroll
-        for (int fn = 0; fn < 2; fn++) { b0[fn] = b_rd[fn] + b_buf; asm volatile("" : "+v"(b0[fn])); }
+        for (int fn = 0; fn < FN; fn++) { b0[fn] = b_rd[fn] + b_buf; asm volatile("" : "+v"(b0[fn])); }
 #pragma unroll
-        for (int s = 0; s < 2; s++) {
-            const int ks = 2 * h + s;
-            uint32_t a0 = a_rd[ks] + a_buf;
+        for (int s = 0; s < NSL / 2; s++) {
+            const int sl = (NSL / 2) * h + s;
+            uint32_t a0 = a_rd[sl] + a_buf;
             asm volatile("" : "+v"(a0));
 #pragma unroll
-            for (int fm = 0; fm < 4; fm++)
-                fa[s][fm] = lds_read_b128(a0 + fm * 32 * (BK * 2));
+            for (int fm = 0; fm < FM; fm++)
+                fa[s][fm] = lds_read_b128(a0 + fm * MI * (BK * 2));
 #pragma unroll
-            for (int fn = 0; fn < 2; fn++) {
-                const half4 lo = lds_read_tr16(b0[fn] + ks * 16 * B_ROW);
-                const half4 hi = lds_read_tr16(b0[fn] + ks * 16 * B_ROW + 4 * B_ROW);
+            for (int fn = 0; fn < FN; fn++) {
+                const half4 lo = lds_read_tr16(b0[fn] + sl * (64 / NSL) * B_ROW);
+                const half4 hi = lds_read_tr16(b0[fn] + sl * (64 / NSL) * B_ROW + 4 * B_ROW);
                 fb[s][fn] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             }
         }
     };
     auto multiply = [&]() {
 #pragma unroll
-        for (int s = 0; s < 2; s++)
+        for (int s = 0; s < NSL / 2; s++)
 #pragma unroll
-            for (int fm = 0; fm < 4; fm++)
+            for (int fm = 0; fm < FM; fm++)
 #pragma unroll
-                for (int fn = 0; fn < 2; fn++)
-                    acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[s][fn], fa[s][fm], acc[fm][fn], 0, 0, 0);   // B first: transposed block
+                for (int fn = 0; fn < FN; fn++) {
+                    // B fragment first: the transposed block
+                    if constexpr (MI == 32) acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[s][fn], fa[s][fm], acc[fm][fn], 0, 0, 0);
+                    else                    acc[fm][fn] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fb[s][fn], fa[s][fm], acc[fm][fn], 0, 0, 0);
+                }
     };
     // A reading phase for half h of k step k: 4 copies for a later step, the
     // fragment reads, then wait for (a) the copies issued two reading phases
@@ -301,7 +321,8 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
         typedef typename CVec4<CT>::type ctx4;
         constexpr int PITCH = 272;
         const uint32_t tbuf = smem_base + (uint32_t)wave * 20480u;
-        const uint32_t w_addr = tbuf + (uint32_t)(lane & 31) * PITCH + (uint32_t)(lane >> 5) * 16;
+        // where this lane's 4 consecutive columns of a block go: row l%MI, column 4*(l/MI) (+ block offsets)
+        const uint32_t w_addr = tbuf + (uint32_t)(lane & (MI - 1)) * PITCH + (uint32_t)(lane / MI) * 16;
         const uint32_t r_addr = tbuf + (uint32_t)(lane >> 4) * PITCH + (uint32_t)(lane & 15) * 16;
         const int orow = lane >> 4, ocol = 4 * (lane & 15);       // this lane's row (of 4) and column in a pass
         const bool col_ok = !edge || (ccol0 + ocol < p.N);         // N is a multiple of 8: all 4 columns or none
@@ -320,13 +341,21 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
 #pragma unroll
         for (int fm = 0; fm < 4; fm++) {
             if (fm + 1 < 4) fetch(fm + 1, cin[(fm + 1) & 1]);
+            if constexpr (MI == 32) {
 #pragma unroll
-            for (int fn = 0; fn < 2; fn++)
+                for (int fn = 0; fn < 2; fn++)
 #pragma unroll
-                for (int g = 0; g < 4; g++) {
-                    const floatx4 v = {acc[fm][fn][4 * g], acc[fm][fn][4 * g + 1], acc[fm][fn][4 * g + 2], acc[fm][fn][4 * g + 3]};
-                    *(__attribute__((address_space(3))) floatx4*)(uintptr_t)(w_addr + (fn * 32 + 8 * g) * 4) = v;
-                }
+                    for (int g = 0; g < 4; g++) {
+                        const floatx4 v = {acc[fm][fn][4 * g], acc[fm][fn][4 * g + 1], acc[fm][fn][4 * g + 2], acc[fm][fn][4 * g + 3]};
+                        *(__attribute__((address_space(3))) floatx4*)(uintptr_t)(w_addr + (fn * 32 + 8 * g) * 4) = v;
+                    }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 2; r++)
+#pragma unroll
+                    for (int fn = 0; fn < 4; fn++)
+                        *(__attribute__((address_space(3))) floatx4*)(uintptr_t)(w_addr + r * 16 * PITCH + fn * 16 * 4) = acc[2 * fm + r][fn];
+            }
 #pragma unroll
             for (int ps = 0; ps < 8; ps++) {
                 const floatx4 s4 = *(__attribute__((address_space(3))) const floatx4*)(uintptr_t)(r_addr + 4 * ps * PITCH);
@@ -348,6 +377,7 @@ int64_t grid_pp256(int64_t M, int64_t N)
     return tm * tn;
 }
 
+template <int MI>
 int launch_pp256(const GemmArgs& a)
 {
     const int64_t g = grid_pp256(a.M, a.N);
@@ -359,15 +389,18 @@ int launch_pp256(const GemmArgs& a)
     p.tiles_n = (int)((a.N + PBN - 1) / PBN);
     p.group_m = 8 < p.tiles_m ? 8 : p.tiles_m;     // an XCD's 32 concurrent tiles form an 8 x 4 block of C
     if (a.c_is_f16)
-        hipLaunchKernelGGL(gemm_pp256_kernel<half_t>, dim3((unsigned)g), dim3(512), 0, a.stream, p);
+        hipLaunchKernelGGL((gemm_pp256_kernel<half_t, MI>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
     else
-        hipLaunchKernelGGL(gemm_pp256_kernel<float>, dim3((unsigned)g), dim3(512), 0, a.stream, p);
+        hipLaunchKernelGGL((gemm_pp256_kernel<float, MI>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
     return hipGetLastError() == hipSuccess ? GEMM_F16_OK : GEMM_F16_ERR_LAUNCH;
 }
 
 const GemmConfigDesc kPingPong = {
-    "pp256x256x64_w2x4", PBM, PBN, BK, 8, 128, 64, PP_LDS, true, launch_pp256, grid_pp256};
+    "pp256x256x64_w2x4", PBM, PBN, BK, 8, 128, 64, PP_LDS, true, launch_pp256<32>, grid_pp256};
+const GemmConfigDesc kPingPong16 = {
+    "pp256x256x64_w2x4_mi16", PBM, PBN, BK, 8, 128, 64, PP_LDS, true, launch_pp256<16>, grid_pp256};
 
 }  // namespace
 
 const GemmConfigDesc* pingpong_config() { return &kPingPong; }
+const GemmConfigDesc* pingpong16_config() { return &kPingPong16; }
