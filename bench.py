@@ -32,11 +32,12 @@ def algorithmic_bytes(M, N, K, c_bytes):
     return 2 * (M * K + K * N) + 2 * M * N * c_bytes
 
 
-def kernel_symbol(tile_name, mode):
+def kernel_symbol(tile_name, mode, K=0):
     """Name of the kernel as it shows in a rocprofv3 kernel trace."""
     ct = "float" if mode == "f32" else "_Float16"
     if tile_name.startswith("pp256"):
-        return f"gemm_pp256_kernel<{ct}>"
+        mi = 16 if "mi16" in tile_name else 32
+        return f"gemm_pp256_kernel<{ct}, {mi}, {'true' if K % 64 else 'false'}>"
     if tile_name.startswith("w4_"):
         return f"gemm_w4_kernel<{ct}>"
     if tile_name.startswith("generic"):
@@ -147,7 +148,7 @@ def main():
         roofline = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None}
     roofline["traffic"] = measured_traffic(r["cfg"]["name"], args.workload, args.mode)
-    roofline.update({"kernel": kernel_symbol(r["cfg"]["name"], args.mode), "avg_launch_ms": round(avg_launch_ms, 5),
+    roofline.update({"kernel": kernel_symbol(r["cfg"]["name"], args.mode, K), "avg_launch_ms": round(avg_launch_ms, 5),
                      "median_launch_ms": round(per[len(per) // 2], 5), "min_launch_ms": round(per[0], 5),
                      "algorithmic_bytes": r["bytes"], "flops": 2 * M * N * K})
 

@@ -76,7 +76,9 @@ template <int MI> struct AccBlock;
 template <> struct AccBlock<32> { typedef floatx16 type; };
 template <> struct AccBlock<16> { typedef floatx4 type; };
 
-template <typename CT, int MI>
+// TAIL = false is the instantiation for K % 64 == 0: the zero-filling register
+// path of the k tail and its branches are not compiled into the hot loop.
+template <typename CT, int MI, bool TAIL>
 __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
 {
     __shared__ __attribute__((aligned(1024))) char smem[PP_LDS];
@@ -127,7 +129,7 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     auto copy_a_half = [&](int s, int half, const uint32_t (&off)[4]) {
         const uint32_t dst = smem_base + A_REGION + (s & 1) * A_BUF + half * (A_BUF / 2);
         const half_t* src = a_tile + (int64_t)s * BK;
-        if (s < kt_full) {
+        if (!TAIL || s < kt_full) {
 #pragma unroll
             for (int t = 0; t < 4; t++) async_copy16(src, off[t], dst + 1024 * (wn + 4 * t));
         } else {                                                       // k tail: through registers, zero beyond K
@@ -144,7 +146,7 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     auto copy_b_half = [&](int s, int half, const uint32_t (&off)[4]) {
         const uint32_t dst = smem_base + B_REGION + (s % 3) * B_BUF + half * (B_BUF / 2);
         const half_t* src = b_tile + ((int64_t)s * BK + half * 32) * p.ldb;
-        if (s < kt_full) {
+        if (!TAIL || s < kt_full) {
 #pragma unroll
             for (int t = 0; t < 4; t++) async_copy16(src, off[t], dst + 1024 * (wn + 4 * t));
         } else {
@@ -388,10 +390,14 @@ int launch_pp256(const GemmArgs& a)
     p.tiles_m = (int)((a.M + PBM - 1) / PBM);
     p.tiles_n = (int)((a.N + PBN - 1) / PBN);
     p.group_m = 8 < p.tiles_m ? 8 : p.tiles_m;     // an XCD's 32 concurrent tiles form an 8 x 4 block of C
-    if (a.c_is_f16)
-        hipLaunchKernelGGL((gemm_pp256_kernel<half_t, MI>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
-    else
-        hipLaunchKernelGGL((gemm_pp256_kernel<float, MI>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
+    const bool tail = (a.K % BK) != 0;
+    if (a.c_is_f16) {
+        if (tail) hipLaunchKernelGGL((gemm_pp256_kernel<half_t, MI, true>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
+        else      hipLaunchKernelGGL((gemm_pp256_kernel<half_t, MI, false>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
+    } else {
+        if (tail) hipLaunchKernelGGL((gemm_pp256_kernel<float, MI, true>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
+        else      hipLaunchKernelGGL((gemm_pp256_kernel<float, MI, false>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
+    }
     return hipGetLastError() == hipSuccess ? GEMM_F16_OK : GEMM_F16_ERR_LAUNCH;
 }
 
