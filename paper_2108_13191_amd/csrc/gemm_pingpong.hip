@@ -11,15 +11,17 @@
 //     128 registers).  Wavefront w and w+4 share a SIMD.
 //   * Time is cut into phases separated by one workgroup barrier.  In a phase
 //     one group reads its A/B fragments of half a k step from LDS into
-//     registers (48 VGPRs) and issues global -> LDS copies, while the other
-//     group issues its 16 MFMAs back to back with every operand already in
-//     registers; then they swap.  The matrix pipe of a SIMD therefore always
-//     has a wavefront that is not waiting on memory.
+//     registers (48 VGPRs), while the other group issues its 16 MFMAs back to
+//     back with every operand already in registers, and between them its 4
+//     global -> LDS copies for two k steps ahead; then they swap.  The matrix
+//     pipe of a SIMD therefore always has a wavefront that is not waiting on
+//     LDS, and the copies (paced by the texture addresser, 16 cycles per 1 KB
+//     wave-wide copy) are spread over the phase instead of queueing up in the
+//     reading phase, which would then outlast the MFMAs.
 //   * 160 KB of LDS hold 2 A buffers (256 x 64 f16 = 32 KB each) and 3 B
-//     buffers (64 x 256 f16 = 32 KB each).  Every copy is issued at least five
-//     phases before its data is read (A halves are recycled as soon as the
-//     group that owns those rows has read them; B needs the third buffer for
-//     that), so a copy has five MFMA phases to cross L2 / Infinity Fabric.
+//     buffers (64 x 256 f16 = 32 KB each).  Each group brings in the A rows it
+//     reads itself (X: A-top, Y: A-bottom) and one k half of B for everybody
+//     (X: B-low = k rows 0-31, Y: B-high = k rows 32-63).
 //   * Copies are global_load_lds_dwordx4 (no register staging); the LDS image
 //     is XOR-swizzled by the choice of the chunk each lane fetches; A
 //     fragments are ds_read_b128, B fragments ds_read_b64_tr_b16 (B is
@@ -27,15 +29,17 @@
 //
 // Schedule (k = k step of 64, cut in halves h = 0,1 of two 16-wide k slices;
 // phase numbers P):
-//   X: P = 4k+2h    read the fragments of (k,h); h=0: issue A-bottom(k+1),
-//                   h=1: issue B-low(k+2)
-//      P = 4k+2h+1  16 MFMAs of (k,h)
-//   Y: the same one phase later; h=0: issue B-high(k+2), h=1: A-top(k+2)
-// ("low/high" = k rows 0-31 / 32-63 of a B stage).  At the end of a reading
-// phase a wavefront waits until the copies it issued two reading phases ago
-// have landed (vmcnt(8): only the 8 issued since may be outstanding), so data
-// is visible to everybody at least five phases after it was requested, and a
-// buffer is overwritten only after its last reader has passed a barrier.
+//   X: P = 4k+2h    read the fragments of (k,h)
+//      P = 4k+2h+1  16 MFMAs of (k,h); h=0: issue B-low(k+2), h=1: A-top(k+2)
+//   Y: the same one phase later; h=0: issue B-high(k+2), h=1: A-bottom(k+2)
+// A-top(k+2) overwrites A-top(k), which X finished reading in the phase
+// before; B-low(k+2) overwrites B-low(k-1), last read by Y five phases earlier
+// (hence the third B buffer).  At the end of the multiplying phase of (k,1) a
+// wavefront waits until its copies for k step k+1 have landed (vmcnt(8): only
+// the 8 issued during this k step may be outstanding) and the barrier that
+// follows publishes them: a copy has four phases (A) or six (B) to cross L2 /
+// Infinity Fabric.  The last two k steps issue no copies and run as a second
+// loop, so that the main loop carries no branch between its MFMAs.
 //
 // The accumulators start at zero; C is read once per tile in the epilogue,
 // where the accumulators pass through LDS so that both the read and the write
@@ -78,6 +82,8 @@ template <> struct AccBlock<16> { typedef floatx4 type; };
 
 // TAIL = false is the instantiation for K % 64 == 0: the zero-filling register
 // path of the k tail and its branches are not compiled into the hot loop.
+template <bool V> struct BoolTag { static constexpr bool value = V; };
+
 template <typename CT, int MI, bool TAIL>
 __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
 {
@@ -125,60 +131,47 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
         return ((uint32_t)(2 * (wn + 4 * t) + b_krow_in_copy) * (uint32_t)p.ldb + col) * 2;
     };
 
-    // one A half of k step s into A buffer s%2; `off` = the caller's 4 lane offsets
-    auto copy_a_half = [&](int s, int half, const uint32_t (&off)[4]) {
-        const uint32_t dst = smem_base + A_REGION + (s & 1) * A_BUF + half * (A_BUF / 2);
+    // Copy t (of 4 per wavefront) of one A half of k step s into A buffer s%2;
+    // `off` = the caller's 4 lane offsets.
+    auto copy_a_part = [&](int s, int half, const uint32_t (&off)[4], int t) {
+        const uint32_t dst = smem_base + A_REGION + (s & 1) * A_BUF + half * (A_BUF / 2) + 1024 * (wn + 4 * t);
         const half_t* src = a_tile + (int64_t)s * BK;
         if (!TAIL || s < kt_full) {
-#pragma unroll
-            for (int t = 0; t < 4; t++) async_copy16(src, off[t], dst + 1024 * (wn + 4 * t));
+            async_copy16(src, off[t], dst);
         } else {                                                       // k tail: through registers, zero beyond K
             const int kvalid = p.K - s * BK;
-#pragma unroll
-            for (int t = 0; t < 4; t++) {
-                uintx4 v = {0u, 0u, 0u, 0u};
-                if (8 * a_chunk < kvalid) v = *reinterpret_cast<const uintx4*>((const char*)src + off[t]);
-                *(__attribute__((address_space(3))) uintx4*)(uintptr_t)(dst + 1024 * (wn + 4 * t) + 16 * lane) = v;
-            }
+            uintx4 v = {0u, 0u, 0u, 0u};
+            if (8 * a_chunk < kvalid) v = *reinterpret_cast<const uintx4*>((const char*)src + off[t]);
+            *(__attribute__((address_space(3))) uintx4*)(uintptr_t)(dst + 16 * lane) = v;
         }
     };
-    // one B half of k step s into B buffer s%3
-    auto copy_b_half = [&](int s, int half, const uint32_t (&off)[4]) {
-        const uint32_t dst = smem_base + B_REGION + (s % 3) * B_BUF + half * (B_BUF / 2);
+    // copy t of one B half of k step s into B buffer s%3
+    auto copy_b_part = [&](int s, int half, const uint32_t (&off)[4], int t) {
+        const uint32_t dst = smem_base + B_REGION + (s % 3) * B_BUF + half * (B_BUF / 2) + 1024 * (wn + 4 * t);
         const half_t* src = b_tile + ((int64_t)s * BK + half * 32) * p.ldb;
         if (!TAIL || s < kt_full) {
-#pragma unroll
-            for (int t = 0; t < 4; t++) async_copy16(src, off[t], dst + 1024 * (wn + 4 * t));
+            async_copy16(src, off[t], dst);
         } else {
             const int kvalid = p.K - s * BK - half * 32;               // valid k rows of this half (may be <= 0)
-#pragma unroll
-            for (int t = 0; t < 4; t++) {
-                uintx4 v = {0u, 0u, 0u, 0u};
-                if (2 * (wn + 4 * t) + b_krow_in_copy < kvalid) v = *reinterpret_cast<const uintx4*>((const char*)src + off[t]);
-                *(__attribute__((address_space(3))) uintx4*)(uintptr_t)(dst + 1024 * (wn + 4 * t) + 16 * lane) = v;
-            }
+            uintx4 v = {0u, 0u, 0u, 0u};
+            if (2 * (wn + 4 * t) + b_krow_in_copy < kvalid) v = *reinterpret_cast<const uintx4*>((const char*)src + off[t]);
+            *(__attribute__((address_space(3))) uintx4*)(uintptr_t)(dst + 16 * lane) = v;
         }
     };
 
-    // steady-state offsets: X copies A-bottom and B-low, Y copies A-top and B-high
+    // X copies A-top and B-low, Y copies A-bottom and B-high: each group brings
+    // in the A rows it reads itself and one k half of B for both groups.
     uint32_t a_off[4], b_off[4];
 #pragma unroll
-    for (int t = 0; t < 4; t++) { a_off[t] = a_offset(1 - grp, t); b_off[t] = b_offset(t); }
+    for (int t = 0; t < 4; t++) { a_off[t] = a_offset(grp, t); b_off[t] = b_offset(t); }
 
-    // ---- prologue: everything the schedule does not cover -------------------
-    // X: A-bottom(0), B-low(0), B-low(1);  Y: A-top(0), A-top(1), B-high(0), B-high(1)
-    {
-        if (grp == 0) {
-            copy_a_half(0, 1, a_off);
-            copy_b_half(0, 0, b_off);
-            if (KT > 1) copy_b_half(1, 0, b_off);
-        } else {
-            copy_a_half(0, 0, a_off);
-            if (KT > 1) copy_a_half(1, 0, a_off);
-            copy_b_half(0, 1, b_off);
-            if (KT > 1) copy_b_half(1, 1, b_off);
+    // ---- prologue: k steps 0 and 1 ---------------------------------------------
+#pragma unroll
+    for (int s = 0; s < 2; s++)
+        if (s < KT) {
+#pragma unroll
+            for (int t = 0; t < 4; t++) { copy_a_part(s, grp, a_off, t); copy_b_part(s, grp, b_off, t); }
         }
-    }
 
     // ---- accumulators -------------------------------------------------------
     // They start at zero; C is read once, in the epilogue, and added there
@@ -258,7 +251,18 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
             }
         }
     };
-    auto multiply = [&]() {
+    // A multiplying phase: the MFMAs of half a k step (k slices of the fragments
+    // just read), with this wavefront's 4 copies for k step k + 2 spread between
+    // them (h = 0: its k half of B, h = 1: its own A rows).  The copies are paced
+    // by the texture addresser (a wave-wide 1 KB copy occupies it for 16
+    // cycles); spread out like this they neither queue up behind each other nor
+    // hold up the MFMAs, which wait for the pipe anyway.  After the last MFMA of
+    // a k step the wavefront waits for its copies for k step k + 1 (in-order
+    // completion: only the 8 issued during this k step may be outstanding), so
+    // that the barrier that follows publishes them.
+    constexpr int NMFMA = (NSL / 2) * FM * FN;
+    auto multiply_phase = [&](int k, int h, auto copy_tag) {
+        constexpr bool COPY = decltype(copy_tag)::value;
 #pragma unroll
         for (int s = 0; s < NSL / 2; s++)
 #pragma unroll
@@ -268,30 +272,29 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
                     // B fragment first: the transposed block
                     if constexpr (MI == 32) acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[s][fn], fa[s][fm], acc[fm][fn], 0, 0, 0);
                     else                    acc[fm][fn] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fb[s][fn], fa[s][fm], acc[fm][fn], 0, 0, 0);
+                    const int idx = (s * FM + fm) * FN + fn;
+                    if (COPY && idx % (NMFMA / 4) == NMFMA / 8 - 1) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (h == 0) copy_b_part(k + 2, grp, b_off, idx / (NMFMA / 4));
+                        else        copy_a_part(k + 2, grp, a_off, idx / (NMFMA / 4));
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
-    };
-    // A reading phase for half h of k step k: 4 copies for a later step, the
-    // fragment reads, then wait for (a) the copies issued two reading phases
-    // ago (only the 8 issued since may be outstanding) and (b) the fragment
-    // reads, so that the barrier that follows publishes both.
-    auto reading_phase = [&](int k, int h) {
-        // LDS reads first: they issue in a few cycles each and complete on their
-        // own.  The copies behind them are paced by the texture addresser (a
-        // wave-wide 1 KB copy occupies it for 16 cycles and the four reading
-        // wavefronts issue theirs together), so they would hold up every
-        // instruction placed after them.
-        read_fragments(k, h);
-        __builtin_amdgcn_sched_barrier(0);
-        if (grp == 0) {
-            if (h == 0) { if (k + 1 < KT) copy_a_half(k + 1, 1, a_off); }
-            else        { if (k + 2 < KT) copy_b_half(k + 2, 0, b_off); }
-        } else {
-            if (h == 0) { if (k + 2 < KT) copy_b_half(k + 2, 1, b_off); }
-            else        { if (k + 2 < KT) copy_a_half(k + 2, 0, a_off); }
+        if (h == 1) {
+            __builtin_amdgcn_sched_barrier(0);
+            if (COPY && (!TAIL || k + 2 < kt_full)) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+            else                                    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
         }
-        if (k + 2 < kt_full) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        else                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    };
+    auto k_step = [&](int k, auto copy_tag) {
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            read_fragments(k, h);          // X: phase 4k + 2h,     Y: 4k + 2h + 1
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            phase_barrier();
+            multiply_phase(k, h, copy_tag);          // X: phase 4k + 2h + 1, Y: 4k + 2h + 2
+            if (decltype(copy_tag)::value || grp == 0 || h == 0 || k + 1 < KT) phase_barrier();
+        }
     };
 
     // prologue copies and the C tile have landed before phase 0
@@ -302,15 +305,10 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     // and leaves out the last barrier, so every wavefront meets the same
     // number of barriers.
     if (grp == 1) phase_barrier();         // phase 0: X reads, Y has nothing to do yet
-    for (int k = 0; k < KT; k++) {
-#pragma unroll
-        for (int h = 0; h < 2; h++) {
-            reading_phase(k, h);           // X: phase 4k + 2h,     Y: 4k + 2h + 1
-            phase_barrier();
-            multiply();                    // X: phase 4k + 2h + 1, Y: 4k + 2h + 2
-            if (grp == 0 || h == 0 || k + 1 < KT) phase_barrier();
-        }
-    }
+    // k steps that issue copies for step k + 2, then the last two, which do not
+    int k = 0;
+    for (; k + 2 < KT; k++) k_step(k, BoolTag<true>{});
+    for (; k < KT; k++) k_step(k, BoolTag<false>{});
 
     // ---- + C, -> C ---------------------------------------------------------------
     // Behind the last barrier nobody reads the A/B buffers any more, so each
