@@ -80,9 +80,11 @@ template <int MI> struct AccBlock;
 template <> struct AccBlock<32> { typedef floatx16 type; };
 template <> struct AccBlock<16> { typedef floatx4 type; };
 
-// TAIL = false is the instantiation for K % 64 == 0: the zero-filling register
-// path of the k tail and its branches are not compiled into the hot loop.
+// TAIL = false is the instantiation for K % 64 == 0.  With TAIL the k step that
+// fetches the k tail (through registers, zero-filled) is a loop of its own, so
+// the main loop is the same in both.
 template <bool V> struct BoolTag { static constexpr bool value = V; };
+template <int V> struct IntTag { static constexpr int value = V; };
 
 template <typename CT, int MI, bool TAIL>
 __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
@@ -132,13 +134,15 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     };
 
     // Copy t (of 4 per wavefront) of one A half of k step s into A buffer s%2;
-    // `off` = the caller's 4 lane offsets.
-    auto copy_a_part = [&](int s, int half, const uint32_t (&off)[4], int t) {
+    // `off` = the caller's 4 lane offsets.  A whole k step goes global -> LDS
+    // directly; the k tail (the last k step when K is not a multiple of 64) goes
+    // through registers, zero beyond K.
+    auto copy_a_part = [&](int s, int half, const uint32_t (&off)[4], int t, auto whole_tag) {
         const uint32_t dst = smem_base + A_REGION + (s & 1) * A_BUF + half * (A_BUF / 2) + 1024 * (wn + 4 * t);
         const half_t* src = a_tile + (int64_t)s * BK;
-        if (!TAIL || s < kt_full) {
+        if constexpr (decltype(whole_tag)::value) {
             async_copy16(src, off[t], dst);
-        } else {                                                       // k tail: through registers, zero beyond K
+        } else {
             const int kvalid = p.K - s * BK;
             uintx4 v = {0u, 0u, 0u, 0u};
             if (8 * a_chunk < kvalid) v = *reinterpret_cast<const uintx4*>((const char*)src + off[t]);
@@ -146,10 +150,10 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
         }
     };
     // copy t of one B half of k step s into B buffer s%3
-    auto copy_b_part = [&](int s, int half, const uint32_t (&off)[4], int t) {
+    auto copy_b_part = [&](int s, int half, const uint32_t (&off)[4], int t, auto whole_tag) {
         const uint32_t dst = smem_base + B_REGION + (s % 3) * B_BUF + half * (B_BUF / 2) + 1024 * (wn + 4 * t);
         const half_t* src = b_tile + ((int64_t)s * BK + half * 32) * p.ldb;
-        if (!TAIL || s < kt_full) {
+        if constexpr (decltype(whole_tag)::value) {
             async_copy16(src, off[t], dst);
         } else {
             const int kvalid = p.K - s * BK - half * 32;               // valid k rows of this half (may be <= 0)
@@ -169,8 +173,13 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
 #pragma unroll
     for (int s = 0; s < 2; s++)
         if (s < KT) {
+            if (!TAIL || s < kt_full) {
 #pragma unroll
-            for (int t = 0; t < 4; t++) { copy_a_part(s, grp, a_off, t); copy_b_part(s, grp, b_off, t); }
+                for (int t = 0; t < 4; t++) { copy_a_part(s, grp, a_off, t, BoolTag<true>{}); copy_b_part(s, grp, b_off, t, BoolTag<true>{}); }
+            } else {
+#pragma unroll
+                for (int t = 0; t < 4; t++) { copy_a_part(s, grp, a_off, t, BoolTag<false>{}); copy_b_part(s, grp, b_off, t, BoolTag<false>{}); }
+            }
         }
 
     // ---- accumulators -------------------------------------------------------
@@ -261,8 +270,11 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     // completion: only the 8 issued during this k step may be outstanding), so
     // that the barrier that follows publishes them.
     constexpr int NMFMA = (NSL / 2) * FM * FN;
+    // copy_tag: 0 no copies (last two k steps), 1 k step k + 2 is a whole one,
+    // 2 it is the k tail
     auto multiply_phase = [&](int k, int h, auto copy_tag) {
-        constexpr bool COPY = decltype(copy_tag)::value;
+        constexpr bool COPY = decltype(copy_tag)::value != 0;
+        typedef BoolTag<decltype(copy_tag)::value == 1> whole_t;
 #pragma unroll
         for (int s = 0; s < NSL / 2; s++)
 #pragma unroll
@@ -275,14 +287,14 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
                     const int idx = (s * FM + fm) * FN + fn;
                     if (COPY && idx % (NMFMA / 4) == NMFMA / 8 - 1) {
                         __builtin_amdgcn_sched_barrier(0);
-                        if (h == 0) copy_b_part(k + 2, grp, b_off, idx / (NMFMA / 4));
-                        else        copy_a_part(k + 2, grp, a_off, idx / (NMFMA / 4));
+                        if (h == 0) copy_b_part(k + 2, grp, b_off, idx / (NMFMA / 4), whole_t{});
+                        else        copy_a_part(k + 2, grp, a_off, idx / (NMFMA / 4), whole_t{});
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
         if (h == 1) {
             __builtin_amdgcn_sched_barrier(0);
-            if (COPY && (!TAIL || k + 2 < kt_full)) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+            if (whole_t::value) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
             else                                    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
         }
     };
@@ -293,7 +305,7 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             phase_barrier();
             multiply_phase(k, h, copy_tag);          // X: phase 4k + 2h + 1, Y: 4k + 2h + 2
-            if (decltype(copy_tag)::value || grp == 0 || h == 0 || k + 1 < KT) phase_barrier();
+            if (decltype(copy_tag)::value != 0 || grp == 0 || h == 0 || k + 1 < KT) phase_barrier();
         }
     };
 
@@ -307,8 +319,9 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     if (grp == 1) phase_barrier();         // phase 0: X reads, Y has nothing to do yet
     // k steps that issue copies for step k + 2, then the last two, which do not
     int k = 0;
-    for (; k + 2 < KT; k++) k_step(k, BoolTag<true>{});
-    for (; k < KT; k++) k_step(k, BoolTag<false>{});
+    for (; k + 2 < kt_full; k++) k_step(k, IntTag<1>{});
+    if constexpr (TAIL) { for (; k + 2 < KT; k++) k_step(k, IntTag<2>{}); }     // at most once: fetches the k tail
+    for (; k < KT; k++) k_step(k, IntTag<0>{});
 
     // ---- + C, -> C ---------------------------------------------------------------
     // Behind the last barrier nobody reads the A/B buffers any more, so each
