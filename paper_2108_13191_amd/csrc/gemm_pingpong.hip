@@ -309,8 +309,11 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
         }
     };
 
-    // prologue copies and the C tile have landed before phase 0
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    // k step 0 has landed before phase 0; the 8 copies of k step 1 (issued
+    // behind it, completing in order) may still be on their way -- the wait at
+    // the end of k step 0 covers them
+    if (1 < kt_full) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else             asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     phase_barrier();
 
     // Both groups run the same loop; Y enters it one phase (one barrier) later
