@@ -9,9 +9,9 @@ namespace {
 
 // Configuration table: entry 0 is the any-shape kernel, entry 1 the 256 x 256
 // four-wavefront kernel, entries 2 and 3 the 256 x 256 phase-alternating
-// eight-wavefront kernel on 32x32x16 and on 16x16x32 MFMAs, the rest the
-// generic double-buffered tiles.
-int num_configs() { return 4 + tiled_num_configs(); }
+// eight-wavefront kernel on 32x32x16 and on 16x16x32 MFMAs, then the generic
+// double-buffered tiles, then the 192- and 128-row forms of entry 3.
+int num_configs() { return 4 + tiled_num_configs() + 2; }
 
 const GemmConfigDesc kGeneric = {
     "generic64x64x32", 64, 64, 32, 4, 32, 32, 2 * 64 * (32 + 8) * 2,
@@ -19,7 +19,9 @@ const GemmConfigDesc kGeneric = {
 
 const GemmConfigDesc* config(int id)
 {
-    return id == 0 ? &kGeneric : id == 1 ? w4_config() : id == 2 ? pingpong_config() : id == 3 ? pingpong16_config() : tiled_config(id - 4);
+    const int nt = tiled_num_configs();
+    if (id >= 4 + nt) return pingpong16_config(id == 4 + nt ? 192 : 128);
+    return id == 0 ? &kGeneric : id == 1 ? w4_config() : id == 2 ? pingpong_config() : id == 3 ? pingpong16_config(256) : tiled_config(id - 4);
 }
 
 int g_forced = -1;
@@ -56,8 +58,10 @@ int select_config(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, c
     if (g_forced >= 0 && g_forced < num_configs()) return g_forced;
     struct Cand { int id; double eff; int per_cu; };
     // ids: 3 = 256x256 (eight wavefronts, phase-alternating, 16x16x32 MFMA: measured
-    // faster than the 32x32x16 form of the same kernel, id 2), 5 = 128x128, 6 = 64x64
-    const Cand cands[] = {{3, 1.0, 1}, {5, 0.7, 2}, {6, 0.4, 4}};
+    // faster than the 32x32x16 form of the same kernel, id 2), 7 and 8 = its 192- and
+    // 128-row forms (less operand reuse per tile, but e.g. 6144^3 is exactly three
+    // rounds of 192x256 tiles instead of 2.25 of 256x256), 5 = 128x128, 6 = 64x64
+    const Cand cands[] = {{3, 1.0, 1}, {7, 0.87, 1}, {8, 0.78, 1}, {5, 0.7, 2}, {6, 0.4, 4}};
     int best = 3;
     double best_cost = 0;
     for (const Cand& c : cands) {

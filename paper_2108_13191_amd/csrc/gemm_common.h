@@ -44,7 +44,7 @@ const GemmConfigDesc* tiled_config(int i);
 
 // gemm_pingpong.hip
 const GemmConfigDesc* pingpong_config();
-const GemmConfigDesc* pingpong16_config();
+const GemmConfigDesc* pingpong16_config(int block_m);   // 256, 192 or 128 rows per tile
 
 // gemm_w4.hip
 const GemmConfigDesc* w4_config();

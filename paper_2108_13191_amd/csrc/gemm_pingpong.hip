@@ -55,12 +55,9 @@ namespace {
 
 using namespace gemm_dev;
 
-constexpr int PBM = 256, PBN = 256;
-constexpr int A_BUF = PBM * BK * 2;          // 32 KB
+constexpr int PBN = 256;
 constexpr int B_BUF = BK * PBN * 2;          // 32 KB
-constexpr int A_REGION = 0;                  // two A buffers
-constexpr int B_REGION = 2 * A_BUF;          // three B buffers
-constexpr int PP_LDS = 2 * A_BUF + 3 * B_BUF;   // 160 KB
+constexpr int A_REGION = 0;                  // two A buffers, then three B buffers
 constexpr int B_ROW = PBN * 2;               // bytes per k row of a B stage
 
 __device__ __forceinline__ void phase_barrier()
@@ -86,9 +83,17 @@ template <> struct AccBlock<16> { typedef floatx4 type; };
 template <bool V> struct BoolTag { static constexpr bool value = V; };
 template <int V> struct IntTag { static constexpr int value = V; };
 
-template <typename CT, int MI, bool TAIL>
+// BM = rows of the workgroup tile: 256, or 192 / 128 for problems whose tile count
+// fills the compute units better that way (the wavefront tile is then 96 x 64 /
+// 64 x 64; everything else is unchanged).
+template <typename CT, int MI, bool TAIL, int BM>
 __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
 {
+    constexpr int HM = BM / 2;                       // rows per wavefront group
+    constexpr int A_BUF = BM * BK * 2;               // 32 KB for BM = 256
+    constexpr int B_REGION = 2 * A_BUF;
+    constexpr int PP_LDS = 2 * A_BUF + 3 * B_BUF;    // 160 KB for BM = 256
+    constexpr int TA = HM / 32;                      // copies per wavefront and A half
     __shared__ __attribute__((aligned(1024))) char smem[PP_LDS];
     const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_ptr_t)smem;
 
@@ -100,8 +105,8 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
 
     int tile_m, tile_n;
     tile_of_block(p, blockIdx.x, tile_m, tile_n);
-    const int m0 = tile_m * PBM, n0 = tile_n * PBN;
-    const bool edge = (m0 + PBM > p.M) || (n0 + PBN > p.N);
+    const int m0 = tile_m * BM, n0 = tile_n * PBN;
+    const bool edge = (m0 + BM > p.M) || (n0 + PBN > p.N);
 
     const int kt_full = p.K / BK;
     const int KT = (p.K + BK - 1) / BK;
@@ -115,7 +120,7 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     const half_t* const b_tile = p.B + n0;
     const int a_chunk = (lane & 7) ^ (4 * (wn & 1) + (lane >> 4));
     auto a_offset = [&](int half, int t) -> uint32_t {
-        int row = half * 128 + 8 * (wn + 4 * t) + (lane >> 3);
+        int row = half * HM + 8 * (wn + 4 * t) + (lane >> 3);
         row = (m0 + row < p.M) ? row : p.M - 1 - m0;                 // clamp: loaded, never stored
         return ((uint32_t)row * (uint32_t)p.lda + 8 * a_chunk) * 2;
     };
@@ -167,7 +172,7 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     // in the A rows it reads itself and one k half of B for both groups.
     uint32_t a_off[4], b_off[4];
 #pragma unroll
-    for (int t = 0; t < 4; t++) { a_off[t] = a_offset(grp, t); b_off[t] = b_offset(t); }
+    for (int t = 0; t < 4; t++) { a_off[t] = t < TA ? a_offset(grp, t) : 0u; b_off[t] = b_offset(t); }
 
     // ---- prologue: k steps 0 and 1 ---------------------------------------------
 #pragma unroll
@@ -175,10 +180,10 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
         if (s < KT) {
             if (!TAIL || s < kt_full) {
 #pragma unroll
-                for (int t = 0; t < 4; t++) { copy_a_part(s, grp, a_off, t, BoolTag<true>{}); copy_b_part(s, grp, b_off, t, BoolTag<true>{}); }
+                for (int t = 0; t < 4; t++) { if (t < TA) copy_a_part(s, grp, a_off, t, BoolTag<true>{}); copy_b_part(s, grp, b_off, t, BoolTag<true>{}); }
             } else {
 #pragma unroll
-                for (int t = 0; t < 4; t++) { copy_a_part(s, grp, a_off, t, BoolTag<false>{}); copy_b_part(s, grp, b_off, t, BoolTag<false>{}); }
+                for (int t = 0; t < 4; t++) { if (t < TA) copy_a_part(s, grp, a_off, t, BoolTag<false>{}); copy_b_part(s, grp, b_off, t, BoolTag<false>{}); }
             }
         }
 
@@ -189,7 +194,7 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     // is row l%32, column 8*(i/4) + 4*(l/32) + i%4 -- 4 consecutive columns per
     // register group, which the epilogue moves 16 bytes at a time.  (16 x 16
     // blocks: register r of lane l is row l%16, column 4*(l/16) + r.)
-    constexpr int FM = 128 / MI, FN = 64 / MI;       // accumulator blocks per wavefront tile
+    constexpr int FM = HM / MI, FN = 64 / MI;        // accumulator blocks per wavefront tile
     typedef typename AccBlock<MI>::type acc_t;       // 16 (MI = 32) or 4 (MI = 16) registers
     acc_t acc[FM][FN];
 #pragma unroll
@@ -199,7 +204,7 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
 #pragma unroll
             for (int i = 0; i < MI * MI / 64; i++) acc[fm][fn][i] = 0.0f;
     CT* const Cbase = (CT*)p.C;
-    const int crow0 = m0 + grp * 128;
+    const int crow0 = m0 + grp * HM;
     const int ccol0 = n0 + wn * 64;
 
     // ---- fragment read addresses ----------------------------------------------
@@ -211,7 +216,7 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     uint32_t a_rd[NSL];
     {
         const int lr = lane & (MI - 1), lk = lane / MI;
-        const uint32_t row_off = (uint32_t)(grp * 128 + lr) * (BK * 2);
+        const uint32_t row_off = (uint32_t)(grp * HM + lr) * (BK * 2);
         const int sw = (lr >> 1) & 7;
 #pragma unroll
         for (int sl = 0; sl < NSL; sl++)
@@ -287,14 +292,18 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
                     const int idx = (s * FM + fm) * FN + fn;
                     if (COPY && idx % (NMFMA / 4) == NMFMA / 8 - 1) {
                         __builtin_amdgcn_sched_barrier(0);
-                        if (h == 0) copy_b_part(k + 2, grp, b_off, idx / (NMFMA / 4), whole_t{});
-                        else        copy_a_part(k + 2, grp, a_off, idx / (NMFMA / 4), whole_t{});
+                        if (h == 0)                       copy_b_part(k + 2, grp, b_off, idx / (NMFMA / 4), whole_t{});
+                        else if (idx / (NMFMA / 4) < TA)  copy_a_part(k + 2, grp, a_off, idx / (NMFMA / 4), whole_t{});
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
         if (h == 1) {
             __builtin_amdgcn_sched_barrier(0);
-            if (whole_t::value) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+            if (whole_t::value) {
+                if constexpr (TA == 4)      asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+                else if constexpr (TA == 3) asm volatile("s_waitcnt vmcnt(7)" ::: "memory");
+                else                        asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+            }
             else                                    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
         }
     };
@@ -312,8 +321,13 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     // k step 0 has landed before phase 0; the 8 copies of k step 1 (issued
     // behind it, completing in order) may still be on their way -- the wait at
     // the end of k step 0 covers them
-    if (1 < kt_full) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-    else             asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    if (1 < kt_full) {
+        if constexpr (TA == 4)      asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else if constexpr (TA == 3) asm volatile("s_waitcnt vmcnt(7)" ::: "memory");
+        else                        asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+    } else {
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    }
     phase_barrier();
 
     // Both groups run the same loop; Y enters it one phase (one barrier) later
@@ -336,7 +350,7 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     {
         typedef typename CVec4<CT>::type ctx4;
         constexpr int PITCH = 272;
-        const uint32_t tbuf = smem_base + (uint32_t)wave * 20480u;
+        const uint32_t tbuf = smem_base + (uint32_t)wave * (32u * PITCH);
         // where this lane's 4 consecutive columns of a block go: row l%MI, column 4*(l/MI) (+ block offsets)
         const uint32_t w_addr = tbuf + (uint32_t)(lane & (MI - 1)) * PITCH + (uint32_t)(lane / MI) * 16;
         const uint32_t r_addr = tbuf + (uint32_t)(lane >> 4) * PITCH + (uint32_t)(lane & 15) * 16;
@@ -355,8 +369,8 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
         };
         fetch(0, cin[0]);
 #pragma unroll
-        for (int fm = 0; fm < 4; fm++) {
-            if (fm + 1 < 4) fetch(fm + 1, cin[(fm + 1) & 1]);
+        for (int fm = 0; fm < HM / 32; fm++) {
+            if (fm + 1 < HM / 32) fetch(fm + 1, cin[(fm + 1) & 1]);
             if constexpr (MI == 32) {
 #pragma unroll
                 for (int fn = 0; fn < 2; fn++)
@@ -386,41 +400,47 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     }
 }
 
-int64_t grid_pp256(int64_t M, int64_t N)
+template <int BM>
+int64_t grid_pp(int64_t M, int64_t N)
 {
-    const int64_t tm = (M + PBM - 1) / PBM, tn = (N + PBN - 1) / PBN;
+    const int64_t tm = (M + BM - 1) / BM, tn = (N + PBN - 1) / PBN;
     if (tm > 0 && tn > INT32_MAX / tm) return -1;
     return tm * tn;
 }
 
-template <int MI>
-int launch_pp256(const GemmArgs& a)
+template <int MI, int BM>
+int launch_pp(const GemmArgs& a)
 {
-    const int64_t g = grid_pp256(a.M, a.N);
+    const int64_t g = grid_pp<BM>(a.M, a.N);
     if (g < 0) return GEMM_F16_ERR_SIZE;
     TiledParams p;
     p.M = (int)a.M; p.N = (int)a.N; p.K = (int)a.K;
     p.A = a.A; p.lda = a.lda; p.B = a.B; p.ldb = a.ldb; p.C = a.C; p.ldc = a.ldc;
-    p.tiles_m = (int)((a.M + PBM - 1) / PBM);
+    p.tiles_m = (int)((a.M + BM - 1) / BM);
     p.tiles_n = (int)((a.N + PBN - 1) / PBN);
     p.group_m = 8 < p.tiles_m ? 8 : p.tiles_m;     // an XCD's 32 concurrent tiles form an 8 x 4 block of C
     const bool tail = (a.K % BK) != 0;
     if (a.c_is_f16) {
-        if (tail) hipLaunchKernelGGL((gemm_pp256_kernel<half_t, MI, true>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
-        else      hipLaunchKernelGGL((gemm_pp256_kernel<half_t, MI, false>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
+        if (tail) hipLaunchKernelGGL((gemm_pp256_kernel<half_t, MI, true, BM>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
+        else      hipLaunchKernelGGL((gemm_pp256_kernel<half_t, MI, false, BM>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
     } else {
-        if (tail) hipLaunchKernelGGL((gemm_pp256_kernel<float, MI, true>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
-        else      hipLaunchKernelGGL((gemm_pp256_kernel<float, MI, false>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
+        if (tail) hipLaunchKernelGGL((gemm_pp256_kernel<float, MI, true, BM>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
+        else      hipLaunchKernelGGL((gemm_pp256_kernel<float, MI, false, BM>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
     }
     return hipGetLastError() == hipSuccess ? GEMM_F16_OK : GEMM_F16_ERR_LAUNCH;
 }
 
+constexpr int lds_pp(int bm) { return 2 * bm * BK * 2 + 3 * B_BUF; }
 const GemmConfigDesc kPingPong = {
-    "pp256x256x64_w2x4", PBM, PBN, BK, 8, 128, 64, PP_LDS, true, launch_pp256<32>, grid_pp256};
+    "pp256x256x64_w2x4", 256, PBN, BK, 8, 128, 64, lds_pp(256), true, launch_pp<32, 256>, grid_pp<256>};
 const GemmConfigDesc kPingPong16 = {
-    "pp256x256x64_w2x4_mi16", PBM, PBN, BK, 8, 128, 64, PP_LDS, true, launch_pp256<16>, grid_pp256};
+    "pp256x256x64_w2x4_mi16", 256, PBN, BK, 8, 128, 64, lds_pp(256), true, launch_pp<16, 256>, grid_pp<256>};
+const GemmConfigDesc kPingPong16_192 = {
+    "pp192x256x64_w2x4_mi16", 192, PBN, BK, 8, 96, 64, lds_pp(192), true, launch_pp<16, 192>, grid_pp<192>};
+const GemmConfigDesc kPingPong16_128 = {
+    "pp128x256x64_w2x4_mi16", 128, PBN, BK, 8, 64, 64, lds_pp(128), true, launch_pp<16, 128>, grid_pp<128>};
 
 }  // namespace
 
 const GemmConfigDesc* pingpong_config() { return &kPingPong; }
-const GemmConfigDesc* pingpong16_config() { return &kPingPong16; }
+const GemmConfigDesc* pingpong16_config(int bm) { return bm == 128 ? &kPingPong16_128 : bm == 192 ? &kPingPong16_192 : &kPingPong16; }
