@@ -80,6 +80,38 @@ int gemm_f16_f16acc(int64_t M, int64_t N, int64_t K,
                     void* C, int64_t ldc,
                     void* stream);
 
+/*
+ * The same two operations with a fused epilogue: a per-column bias and an
+ * optional ReLU applied to each result before its single store (the paper's
+ * Background section, subsection Tensor Cores, names bias addition as the
+ * fusion that needs the thread-data mapping of the accumulators, and its
+ * Conclusion names fusion as the goal; with MFMA the mapping is documented,
+ * so the epilogue is a few instructions in the store path):
+ *
+ *     C[i][j] <- act( C[i][j] + sum_k A[i][k] * B[k][j] + bias[j] )
+ *
+ * bias: N elements of C's type (f32 resp. f16) in device memory, any element
+ * alignment, or NULL for no bias.  act: GEMM_F16_ACT_NONE or
+ * GEMM_F16_ACT_RELU (x < 0 ? 0 : x, so NaN and -0 pass through); any other
+ * value returns GEMM_F16_ERR_CONFIG.  In f32 the sum, C and the bias are added
+ * in that order; in the f16 mode all three are widened exactly, added in f32
+ * and rounded once.  K == 0 applies the epilogue to C alone; M == 0 or N == 0
+ * does nothing.  Everything else as for the plain entry points.
+ */
+enum { GEMM_F16_ACT_NONE = 0, GEMM_F16_ACT_RELU = 1 };
+int gemm_f16_f32acc_bias_act(int64_t M, int64_t N, int64_t K,
+                             const void* A, int64_t lda,
+                             const void* B, int64_t ldb,
+                             float* C, int64_t ldc,
+                             const float* bias, int act,
+                             void* stream);
+int gemm_f16_f16acc_bias_act(int64_t M, int64_t N, int64_t K,
+                             const void* A, int64_t lda,
+                             const void* B, int64_t ldb,
+                             void* C, int64_t ldc,
+                             const void* bias, int act,
+                             void* stream);
+
 /* Static, human-readable text for a return code. Never NULL. */
 const char* gemm_strerror(int code);
 

@@ -7,7 +7,10 @@ this file only builds that C file with gcc and marshals numpy arrays to it.
 
 What is computed (paper, Evaluation section: C = A B + C, row-major; Listing
 "Naive affine matmul"): C_ref = C0 + sum_k A[i,k] B[k,j] in binary64 in
-increasing k, and S = sum_k |A[i,k]| |B[k,j]|.
+increasing k, and S = sum_k |A[i,k]| |B[k,j]|.  The fused epilogue (bias
+addition named in the paper's Background section, subsection Tensor Cores, as
+the fusion that needs the accumulators' thread-data mapping) is the two plain
+numpy lines of `bias_act`.
 """
 from __future__ import annotations
 
@@ -106,6 +109,18 @@ def gemm_f16(A: np.ndarray, B: np.ndarray, C0: np.ndarray, rows=None):
     if rc != 0:
         raise RuntimeError(f"oracle_gemm_f16_rows failed with code {rc}")
     return Cref, S
+
+
+def bias_act(Cref: np.ndarray, bias=None, relu: bool = False) -> np.ndarray:
+    """act(C_ref + bias[j]) in binary64: the per-column bias (any float dtype,
+    widened exactly) is added to every row; ReLU is x < 0 ? 0 : x, so NaN and
+    -0 pass through.  Cref is the binary64 output of gemm_f16."""
+    out = np.array(Cref, dtype=np.float64, copy=True)
+    if bias is not None:
+        out = out + np.asarray(bias).astype(np.float64)[None, :]
+    if relu:
+        out = np.where(out < 0.0, 0.0, out)
+    return out
 
 
 def f16_bits_to_f64(bits: np.ndarray) -> np.ndarray:

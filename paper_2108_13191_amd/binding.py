@@ -51,6 +51,10 @@ def load() -> ctypes.CDLL:
             f = getattr(lib, name)
             f.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
             f.restype = ci
+        for name in ("gemm_f16_f32acc_bias_act", "gemm_f16_f16acc_bias_act"):
+            f = getattr(lib, name)
+            f.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, ci, vp]
+            f.restype = ci
         lib.gemm_strerror.argtypes = [ci]
         lib.gemm_strerror.restype = ctypes.c_char_p
         lib.gemm_f16_query_config.argtypes = [ci, i64, i64, i64, vp, i64, vp, i64, vp, i64,
@@ -82,6 +86,19 @@ def gemm_f16_f32acc(M, N, K, A, lda, B, ldb, C, ldc, stream=0) -> int:
 def gemm_f16_f16acc(M, N, K, A, lda, B, ldb, C, ldc, stream=0) -> int:
     """C (f16) += A (f16) @ B (f16), f32 accumulation, one rounding on store."""
     return load().gemm_f16_f16acc(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, _ptr(stream))
+
+
+ACT_NONE, ACT_RELU = 0, 1
+
+
+def gemm_f16_f32acc_bias_act(M, N, K, A, lda, B, ldb, C, ldc, bias, act, stream=0) -> int:
+    """C (f32) = act(C + A @ B + bias[None, :]); bias f32 device vector or None."""
+    return load().gemm_f16_f32acc_bias_act(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, _ptr(bias), act, _ptr(stream))
+
+
+def gemm_f16_f16acc_bias_act(M, N, K, A, lda, B, ldb, C, ldc, bias, act, stream=0) -> int:
+    """C (f16) = act(C + A @ B + bias[None, :]), f32 arithmetic, one rounding on store; bias f16 or None."""
+    return load().gemm_f16_f16acc_bias_act(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, _ptr(bias), act, _ptr(stream))
 
 
 def strerror(code: int) -> str:

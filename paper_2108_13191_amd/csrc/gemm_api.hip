@@ -87,12 +87,25 @@ void fill_desc(int id, int64_t grid, gemm_f16_config* out)
 }
 
 int run(int c_is_f16, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
-        const void* B, int64_t ldb, void* C, int64_t ldc, void* stream)
+        const void* B, int64_t ldb, void* C, int64_t ldc, void* stream,
+        const void* bias = nullptr, int act = GEMM_F16_ACT_NONE)
 {
     const int rc = check_args(c_is_f16, M, N, K, A, lda, B, ldb, C, ldc);
     if (rc != GEMM_F16_OK) return rc;
-    if (M == 0 || N == 0 || K == 0) return GEMM_F16_OK;   // C + empty sum = C
+    if (act != GEMM_F16_ACT_NONE && act != GEMM_F16_ACT_RELU) return GEMM_F16_ERR_CONFIG;
+    if ((uintptr_t)bias & (c_is_f16 ? 1 : 3)) return GEMM_F16_ERR_ALIGN;
+    if (M == 0 || N == 0) return GEMM_F16_OK;
+    const bool fused = bias != nullptr || act != GEMM_F16_ACT_NONE;
+    if (K == 0 && !fused) return GEMM_F16_OK;             // C + empty sum = C
     GemmArgs a;
+    a.bias = bias; a.relu = act == GEMM_F16_ACT_RELU;
+    if (K == 0) {
+        // the epilogue alone: the any-shape kernel with an empty k loop (it never touches A or B then)
+        a.M = M; a.N = N; a.K = 0;
+        a.A = (const half_t*)A; a.lda = lda; a.B = (const half_t*)B; a.ldb = ldb; a.C = C; a.ldc = ldc;
+        a.c_is_f16 = c_is_f16; a.stream = (hipStream_t)stream;
+        return config(0)->launch(a);
+    }
     a.M = M; a.N = N; a.K = K;
     a.A = (const half_t*)A; a.lda = lda; a.B = (const half_t*)B; a.ldb = ldb; a.C = C; a.ldc = ldc;
     a.c_is_f16 = c_is_f16; a.stream = (hipStream_t)stream;
@@ -115,6 +128,20 @@ int gemm_f16_f16acc(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
     return run(1, M, N, K, A, lda, B, ldb, C, ldc, stream);
 }
 
+int gemm_f16_f32acc_bias_act(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                             const void* B, int64_t ldb, float* C, int64_t ldc,
+                             const float* bias, int act, void* stream)
+{
+    return run(0, M, N, K, A, lda, B, ldb, C, ldc, stream, bias, act);
+}
+
+int gemm_f16_f16acc_bias_act(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                             const void* B, int64_t ldb, void* C, int64_t ldc,
+                             const void* bias, int act, void* stream)
+{
+    return run(1, M, N, K, A, lda, B, ldb, C, ldc, stream, bias, act);
+}
+
 const char* gemm_strerror(int code)
 {
     switch (code) {
@@ -123,7 +150,7 @@ const char* gemm_strerror(int code)
     case GEMM_F16_ERR_PITCH: return "a leading dimension is smaller than the row length or too large";
     case GEMM_F16_ERR_NULL: return "a required pointer is NULL";
     case GEMM_F16_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
-    case GEMM_F16_ERR_CONFIG: return "unknown configuration id or bad query argument";
+    case GEMM_F16_ERR_CONFIG: return "unknown configuration id, activation or bad query argument";
     case GEMM_F16_ERR_ALIGN: return "a pointer is not aligned to its element size";
     default: return "unknown error code";
     }

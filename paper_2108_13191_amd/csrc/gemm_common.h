@@ -23,6 +23,8 @@ struct GemmArgs {
     void* C; int64_t ldc;
     int c_is_f16;
     hipStream_t stream;
+    const void* bias;      // N elements of C's type, or nullptr
+    int relu;              // 0 / 1
 };
 
 // Static description of one kernel configuration.

@@ -15,7 +15,17 @@ struct TiledParams {
     const half_t* B; int64_t ldb;
     void* C; int64_t ldc;
     int tiles_m, tiles_n, group_m;
+    const void* bias;      // fused epilogue: N elements of C's type or nullptr; relu 0 / 1
+    int relu;
 };
+
+// The fused epilogue on one result: + bias, then ReLU written so that NaN and
+// -0 pass through.
+__device__ __forceinline__ float epilogue_value(float v, float bias, int relu)
+{
+    v += bias;
+    return (relu && v < 0.0f) ? 0.0f : v;
+}
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef __attribute__((address_space(1))) const void* gbl_ptr_t;
@@ -95,10 +105,14 @@ __device__ __forceinline__ void load_c_tile(floatx16 (&acc)[FM][FN], const CT* C
 
 template <typename CT, int FM, int FN>
 __device__ __forceinline__ void store_c_tile(const floatx16 (&acc)[FM][FN], CT* C, int64_t ldc,
-                                             int row0, int col0, int lane, int M, int N, bool edge)
+                                             int row0, int col0, int lane, int M, int N, bool edge,
+                                             const CT* bias, int relu)
 {
     const uint32_t voff = ((uint32_t)(4 * (lane >> 5)) * (uint32_t)ldc + (uint32_t)(lane & 31)) * (uint32_t)sizeof(CT);
     const int lrow = 4 * (lane >> 5), lcol = lane & 31;
+    float b[FN];
+#pragma unroll
+    for (int fn = 0; fn < FN; fn++) b[fn] = (bias && col0 + fn * 32 + lcol < N) ? (float)bias[col0 + fn * 32 + lcol] : 0.0f;
 #pragma unroll
     for (int fm = 0; fm < FM; fm++)
 #pragma unroll
@@ -108,7 +122,7 @@ __device__ __forceinline__ void store_c_tile(const floatx16 (&acc)[FM][FN], CT* 
 #pragma unroll
             for (int fn = 0; fn < FN; fn++)
                 if (!edge || (r + lrow < M && col0 + fn * 32 + lcol < N))
-                    *reinterpret_cast<CT*>(rowp + voff + fn * 32 * sizeof(CT)) = (CT)acc[fm][fn][i];   // f16: one rounding, to nearest even
+                    *reinterpret_cast<CT*>(rowp + voff + fn * 32 * sizeof(CT)) = (CT)epilogue_value(acc[fm][fn][i], b[fn], relu);   // f16: one rounding, to nearest even
         }
 }
 

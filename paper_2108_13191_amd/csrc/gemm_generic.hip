@@ -14,7 +14,8 @@ constexpr int GBM = 64, GBN = 64, GBK = 32, GPAD = 8;
 template <typename CT>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(
     int M, int N, int K, const half_t* __restrict__ A, int64_t lda,
-    const half_t* __restrict__ B, int64_t ldb, CT* __restrict__ C, int64_t ldc, int tiles_n)
+    const half_t* __restrict__ B, int64_t ldb, CT* __restrict__ C, int64_t ldc, int tiles_n,
+    const CT* __restrict__ bias, int relu)
 {
     // A tile as [m][k], B tile transposed to [n][k]: both MFMA operands then
     // read 8 consecutive k per lane with one 16-byte LDS load.
@@ -60,10 +61,14 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
         __syncthreads();
     }
 
+    const float bv = (bias && col < N) ? (float)bias[col] : 0.0f;     // fused epilogue: + bias, ReLU (NaN, -0 pass)
 #pragma unroll
     for (int i = 0; i < 16; i++) {
         const int64_t row = m0 + wm * 32 + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
-        if (row < M && col < N) C[row * ldc + col] = (CT)acc[i];   // f16: round to nearest even
+        if (row < M && col < N) {                                  // f16: round to nearest even
+            float v = acc[i] + bv;
+            C[row * ldc + col] = (CT)((relu && v < 0.0f) ? 0.0f : v);
+        }
     }
 }
 
@@ -83,9 +88,9 @@ int launch_generic(const GemmArgs& a)
     const int tiles_n = (int)((a.N + GBN - 1) / GBN);
     if (a.c_is_f16)
         hipLaunchKernelGGL(gemm_generic_kernel<half_t>, dim3((unsigned)g), dim3(256), 0, a.stream,
-                           (int)a.M, (int)a.N, (int)a.K, a.A, a.lda, a.B, a.ldb, (half_t*)a.C, a.ldc, tiles_n);
+                           (int)a.M, (int)a.N, (int)a.K, a.A, a.lda, a.B, a.ldb, (half_t*)a.C, a.ldc, tiles_n, (const half_t*)a.bias, a.relu);
     else
         hipLaunchKernelGGL(gemm_generic_kernel<float>, dim3((unsigned)g), dim3(256), 0, a.stream,
-                           (int)a.M, (int)a.N, (int)a.K, a.A, a.lda, a.B, a.ldb, (float*)a.C, a.ldc, tiles_n);
+                           (int)a.M, (int)a.N, (int)a.K, a.A, a.lda, a.B, a.ldb, (float*)a.C, a.ldc, tiles_n, (const float*)a.bias, a.relu);
     return hipGetLastError() == hipSuccess ? GEMM_F16_OK : GEMM_F16_ERR_LAUNCH;
 }

@@ -357,6 +357,11 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
         const int orow = lane >> 4, ocol = 4 * (lane & 15);       // this lane's row (of 4) and column in a pass
         const bool col_ok = !edge || (ccol0 + ocol < p.N);         // N is a multiple of 8: all 4 columns or none
         CT* const cptr = Cbase + (int64_t)(crow0 + orow) * p.ldc + ccol0 + ocol;
+        float bias4[4] = {0.0f, 0.0f, 0.0f, 0.0f};              // fused epilogue: this lane's 4 columns of the bias
+        if (p.bias && col_ok) {
+#pragma unroll
+            for (int e = 0; e < 4; e++) bias4[e] = (float)reinterpret_cast<const CT*>(p.bias)[ccol0 + ocol + e];
+        }
         ctx4 cin[2][8];
         auto fetch = [&](int fm, ctx4 (&dst)[8]) {
 #pragma unroll
@@ -392,7 +397,7 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
                 const ctx4 c4 = cin[fm & 1][ps];
                 ctx4 o;
 #pragma unroll
-                for (int e = 0; e < 4; e++) o[e] = (CT)(s4[e] + (float)c4[e]);      // f16: one rounding, to nearest even
+                for (int e = 0; e < 4; e++) o[e] = (CT)epilogue_value(s4[e] + (float)c4[e], bias4[e], p.relu);      // f16: one rounding, to nearest even
                 if (col_ok && (!edge || (crow0 + fm * 32 + 4 * ps + orow < p.M)))
                     *reinterpret_cast<ctx4*>(cptr + (int64_t)(fm * 32 + 4 * ps) * p.ldc) = o;
             }
@@ -416,6 +421,7 @@ int launch_pp(const GemmArgs& a)
     TiledParams p;
     p.M = (int)a.M; p.N = (int)a.N; p.K = (int)a.K;
     p.A = a.A; p.lda = a.lda; p.B = a.B; p.ldb = a.ldb; p.C = a.C; p.ldc = a.ldc;
+    p.bias = a.bias; p.relu = a.relu;
     p.tiles_m = (int)((a.M + BM - 1) / BM);
     p.tiles_n = (int)((a.N + PBN - 1) / PBN);
     p.group_m = 8 < p.tiles_m ? 8 : p.tiles_m;     // an XCD's 32 concurrent tiles form an 8 x 4 block of C

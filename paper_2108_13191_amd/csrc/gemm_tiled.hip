@@ -253,7 +253,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_tiled_kernel(cons
         int64_t ldc2 = p.ldc;
         CT* C2 = Cbase;
         asm volatile("" : "+s"(Mb), "+s"(Nb), "+s"(row2), "+s"(col2), "+s"(ldc2), "+s"(C2), "+v"(lane2));
-        store_c_tile<CT, FM, FN>(acc, C2, ldc2, row2, col2, lane2, Mb, Nb, edge);
+        store_c_tile<CT, FM, FN>(acc, C2, ldc2, row2, col2, lane2, Mb, Nb, edge, (const CT*)p.bias, p.relu);
     }
 }
 
@@ -273,6 +273,7 @@ int launch_tiled(const GemmArgs& a)
     TiledParams p;
     p.M = (int)a.M; p.N = (int)a.N; p.K = (int)a.K;
     p.A = a.A; p.lda = a.lda; p.B = a.B; p.ldb = a.ldb; p.C = a.C; p.ldc = a.ldc;
+    p.bias = a.bias; p.relu = a.relu;
     p.tiles_m = (int)((a.M + BM - 1) / BM);
     p.tiles_n = (int)((a.N + BN - 1) / BN);
     // 32 workgroups of an XCD that run together should form a near-square block of C

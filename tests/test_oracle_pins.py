@@ -287,3 +287,42 @@ def test_error_codes(oracle_mod):
     assert f(2, 2, 2, p, 2, p, 2, p, 1, 0, p, p) == -2
     assert f(2, 2, 2, None, 2, p, 2, p, 2, 0, p, p) == -3
     assert f(2, 2, 2, p, 2, p, 2, p, 2, 0, p, p) == 0
+
+
+# ---- the fused epilogue step (bias per column, ReLU) ----------------------------
+def test_bias_act_closed_forms(oracle_mod):
+    """Pins that do not retype the formula: hand-written values, exact rational
+    arithmetic element by element, and special values."""
+    C = np.array([[1.5, -2.0, 0.25], [-0.5, 4.0, -8.0]])
+    bias = np.array([-1.0, 0.5, 8.0], dtype=np.float32)
+    assert np.array_equal(oracle_mod.bias_act(C, bias, False), [[0.5, -1.5, 8.25], [-1.5, 4.5, 0.0]])
+    assert np.array_equal(oracle_mod.bias_act(C, bias, True), [[0.5, 0.0, 8.25], [0.0, 4.5, 0.0]])
+    assert np.array_equal(oracle_mod.bias_act(C, None, True), [[1.5, 0.0, 0.25], [0.0, 4.0, 0.0]])
+    assert np.array_equal(oracle_mod.bias_act(C, None, False), C)
+    # the bias belongs to the column, not the row: a transposed-operand slip fails here
+    wide = oracle_mod.bias_act(np.zeros((3, 4)), np.array([1.0, 2.0, 3.0, 4.0]), False)
+    assert np.array_equal(wide, np.tile([1.0, 2.0, 3.0, 4.0], (3, 1)))
+    # exact rationals, other loop order
+    rng = np.random.default_rng(4)
+    Cr = rng.integers(-64, 65, size=(5, 7)) / 8.0
+    b16 = (rng.integers(-64, 65, size=7) / 16.0).astype(np.float16)
+    got = oracle_mod.bias_act(Cr, b16, True)
+    for j in range(7):
+        for i in range(5):
+            v = Fraction(float(Cr[i, j])) + Fraction(float(b16[j]))
+            assert Fraction(float(got[i, j])) == (v if v >= 0 else 0)
+    # NaN and -0 pass through ReLU, +/-inf behave as numbers
+    s = oracle_mod.bias_act(np.array([[np.nan, -0.0, np.inf, -np.inf]]), None, True)
+    assert np.isnan(s[0, 0]) and s[0, 1] == 0 and np.signbit(s[0, 1]) and s[0, 2] == np.inf and s[0, 3] == 0
+    # input is not modified
+    assert C[0, 1] == -2.0
+
+
+def test_bias_act_composes_with_gemm(oracle_mod):
+    """relu(C0 + A B + bias) on integer inputs against numpy's exact float64 matmul."""
+    A, B, C0 = wl.make_inputs(24, 40, 16, "int2", "zeros", seed=11)
+    C0[:] = np.arange(24 * 40).reshape(24, 40) % 5 - 2
+    bias = (np.arange(40) % 7 - 3).astype(np.float32)
+    Cref, _ = oracle_mod.gemm_f16(A, B, C0)
+    want = np.maximum(A.astype(np.float64) @ B.astype(np.float64) + C0 + bias[None, :], 0.0)
+    assert np.array_equal(oracle_mod.bias_act(Cref, bias, True), want)
