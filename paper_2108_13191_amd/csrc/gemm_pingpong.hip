@@ -43,7 +43,9 @@
 //
 // The accumulators start at zero; C is read once per tile in the epilogue,
 // where the accumulators pass through LDS so that both the read and the write
-// of C are whole row segments, 16 bytes per lane.
+// of C are whole row segments, 16 bytes per lane.  The first 32 rows (64 for
+// f16 C) of each wavefront's part of C are requested before the last two k
+// steps, which issue no copies, so that they arrive under those MFMAs.
 //
 // Requirements as for the other tuned kernels: A, B 16-byte aligned; lda, ldb,
 // K, N multiples of 8.  Rows >= M / columns >= N are fetched from clamped
@@ -275,6 +277,7 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     // completion: only the 8 issued during this k step may be outstanding), so
     // that the barrier that follows publishes them.
     constexpr int NMFMA = (NSL / 2) * FM * FN;
+    constexpr int NPRE = (sizeof(CT) == 2) ? 2 : 1;     // slabs of 32 C rows requested before the last two k steps
     // copy_tag: 0 no copies (last two k steps), 1 k step k + 2 is a whole one,
     // 2 it is the k tail
     auto multiply_phase = [&](int k, int h, auto copy_tag) {
@@ -304,7 +307,13 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
                 else if constexpr (TA == 3) asm volatile("s_waitcnt vmcnt(7)" ::: "memory");
                 else                        asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
             }
-            else                                    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            else if constexpr (decltype(copy_tag)::value == 0) {
+                // the last two k steps: only the early C loads (8 per slab) may be outstanding
+                if constexpr (NPRE == 2) asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
+                else                     asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+            } else {
+                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            }
         }
     };
     auto k_step = [&](int k, auto copy_tag) {
@@ -338,44 +347,52 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     int k = 0;
     for (; k + 2 < kt_full; k++) k_step(k, IntTag<1>{});
     if constexpr (TAIL) { for (; k + 2 < KT; k++) k_step(k, IntTag<2>{}); }     // at most once: fetches the k tail
+
+    // ---- C: addresses, and the first rows on their way -----------------------------
+    // The last two k steps issue no copies; the first 32 rows of this wavefront's
+    // part of C (64 for f16 C) are requested here, so that they arrive while those
+    // k steps are multiplied (loads complete in order: the waits of those k steps
+    // leave exactly these loads outstanding).
+    typedef typename CVec4<CT>::type ctx4;
+    constexpr int PITCH = 272;
+    const uint32_t tbuf = smem_base + (uint32_t)wave * (32u * PITCH);
+    // where this lane's 4 consecutive columns of a block go: row l%MI, column 4*(l/MI) (+ block offsets)
+    const uint32_t w_addr = tbuf + (uint32_t)(lane & (MI - 1)) * PITCH + (uint32_t)(lane / MI) * 16;
+    const uint32_t r_addr = tbuf + (uint32_t)(lane >> 4) * PITCH + (uint32_t)(lane & 15) * 16;
+    const int orow = lane >> 4, ocol = 4 * (lane & 15);       // this lane's row (of 4) and column in a pass
+    const bool col_ok = !edge || (ccol0 + ocol < p.N);         // N is a multiple of 8: all 4 columns or none
+    CT* const cptr = Cbase + (int64_t)(crow0 + orow) * p.ldc + ccol0 + ocol;
+    float bias4[4] = {0.0f, 0.0f, 0.0f, 0.0f};              // fused epilogue: this lane's 4 columns of the bias
+    if (p.bias && col_ok) {
+#pragma unroll
+        for (int e = 0; e < 4; e++) bias4[e] = (float)reinterpret_cast<const CT*>(p.bias)[ccol0 + ocol + e];
+    }
+    ctx4 cin[2][8];
+    auto fetch = [&](int fm, ctx4 (&dst)[8]) {
+#pragma unroll
+        for (int ps = 0; ps < 8; ps++) {
+            const bool ok = col_ok && (!edge || (crow0 + fm * 32 + 4 * ps + orow < p.M));
+            // a group outside C reads this lane's first (valid or clamped) group of the tile instead
+            const CT* src = ok ? cptr + (int64_t)(fm * 32 + 4 * ps) * p.ldc : Cbase + (int64_t)m0 * p.ldc + n0;
+            dst[ps] = *reinterpret_cast<const ctx4*>(src);
+        }
+    };
+#pragma unroll
+    for (int f = 0; f < NPRE; f++) fetch(f, cin[f]);
+    __builtin_amdgcn_sched_barrier(0);
     for (; k < KT; k++) k_step(k, IntTag<0>{});
 
     // ---- + C, -> C ---------------------------------------------------------------
     // Behind the last barrier nobody reads the A/B buffers any more, so each
-    // wavefront takes 20 KB of LDS as a private transposing buffer: 32 rows x
+    // wavefront takes 8.5 KB of LDS as a private transposing buffer: 32 rows x
     // 64 columns of its accumulators at a time go in as they sit in registers
     // (16 bytes per lane, row pitch 272 B: conflict-free) and come back with 16
     // lanes covering one row, so that C is read and written in whole 256-byte
     // row segments (128 B for f16 C), 16 bytes (8) per lane.
     {
-        typedef typename CVec4<CT>::type ctx4;
-        constexpr int PITCH = 272;
-        const uint32_t tbuf = smem_base + (uint32_t)wave * (32u * PITCH);
-        // where this lane's 4 consecutive columns of a block go: row l%MI, column 4*(l/MI) (+ block offsets)
-        const uint32_t w_addr = tbuf + (uint32_t)(lane & (MI - 1)) * PITCH + (uint32_t)(lane / MI) * 16;
-        const uint32_t r_addr = tbuf + (uint32_t)(lane >> 4) * PITCH + (uint32_t)(lane & 15) * 16;
-        const int orow = lane >> 4, ocol = 4 * (lane & 15);       // this lane's row (of 4) and column in a pass
-        const bool col_ok = !edge || (ccol0 + ocol < p.N);         // N is a multiple of 8: all 4 columns or none
-        CT* const cptr = Cbase + (int64_t)(crow0 + orow) * p.ldc + ccol0 + ocol;
-        float bias4[4] = {0.0f, 0.0f, 0.0f, 0.0f};              // fused epilogue: this lane's 4 columns of the bias
-        if (p.bias && col_ok) {
-#pragma unroll
-            for (int e = 0; e < 4; e++) bias4[e] = (float)reinterpret_cast<const CT*>(p.bias)[ccol0 + ocol + e];
-        }
-        ctx4 cin[2][8];
-        auto fetch = [&](int fm, ctx4 (&dst)[8]) {
-#pragma unroll
-            for (int ps = 0; ps < 8; ps++) {
-                const bool ok = col_ok && (!edge || (crow0 + fm * 32 + 4 * ps + orow < p.M));
-                // a group outside C reads this lane's first (valid or clamped) group of the tile instead
-                const CT* src = ok ? cptr + (int64_t)(fm * 32 + 4 * ps) * p.ldc : Cbase + (int64_t)m0 * p.ldc + n0;
-                dst[ps] = *reinterpret_cast<const ctx4*>(src);
-            }
-        };
-        fetch(0, cin[0]);
 #pragma unroll
         for (int fm = 0; fm < HM / 32; fm++) {
-            if (fm + 1 < HM / 32) fetch(fm + 1, cin[(fm + 1) & 1]);
+            if (fm + 1 < HM / 32 && fm + 1 >= NPRE) fetch(fm + 1, cin[(fm + 1) & 1]);
             if constexpr (MI == 32) {
 #pragma unroll
                 for (int fn = 0; fn < 2; fn++)
