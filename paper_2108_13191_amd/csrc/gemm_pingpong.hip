@@ -1,5 +1,7 @@
-// The large-problem kernel: 256 x 256 C tile per workgroup, 8 wavefronts, k
-// steps of 64, f16 MFMA (v_mfma_f32_32x32x16_f16) with f32 accumulators.
+// The large-problem kernel: 256 x 256 C tile per workgroup (also built with 192
+// and 128 rows), 8 wavefronts, k steps of 64, f16 MFMA with f32 accumulators
+// (v_mfma_f32_16x16x32_f16 in the default configuration, v_mfma_f32_32x32x16_f16
+// in the other; the text below counts in the latter's 32 x 32 blocks).
 //
 // The steps are those of the paper's recipe (Algorithm "Two-level tiled tensor
 // core Matmul"; C hoisted out of the k loop, section "Generating WMMA Ops and
@@ -39,7 +41,8 @@
 // the 8 issued during this k step may be outstanding) and the barrier that
 // follows publishes them: a copy has four phases (A) or six (B) to cross L2 /
 // Infinity Fabric.  The last two k steps issue no copies and run as a second
-// loop, so that the main loop carries no branch between its MFMAs.
+// loop (and, when K is not a multiple of 64, the k step that fetches the k
+// tail as a third), so that the main loop carries no branch between its MFMAs.
 //
 // The accumulators start at zero; C is read once per tile in the epilogue,
 // where the accumulators pass through LDS so that both the read and the write
@@ -79,11 +82,12 @@ template <int MI> struct AccBlock;
 template <> struct AccBlock<32> { typedef floatx16 type; };
 template <> struct AccBlock<16> { typedef floatx4 type; };
 
+template <bool V> struct BoolTag { static constexpr bool value = V; };
+template <int V> struct IntTag { static constexpr int value = V; };
+
 // TAIL = false is the instantiation for K % 64 == 0.  With TAIL the k step that
 // fetches the k tail (through registers, zero-filled) is a loop of its own, so
 // the main loop is the same in both.
-template <bool V> struct BoolTag { static constexpr bool value = V; };
-template <int V> struct IntTag { static constexpr int value = V; };
 
 // BM = rows of the workgroup tile: 256, or 192 / 128 for problems whose tile count
 // fills the compute units better that way (the wavefront tile is then 96 x 64 /
