@@ -196,3 +196,52 @@ def test_non_default_stream(oracle_mod):
         got = run_gemm(A, B, C0, "f32")
     Cref, S = oracle_mod.gemm_f16(A, B, C0)
     assert_close(got, Cref, S, C0, "f32")
+
+
+def test_two_streams_concurrently(oracle_mod):
+    """Two different problems enqueued on two streams without ordering between
+    them: the library keeps no per-call state, so both must come out right."""
+    from gpu_util import DevMat
+    cases = []
+    for seed, (M, N, K) in enumerate([(1536, 1280, 2048), (1100, 2056, 1544)]):
+        A, B, C0 = wl.make_inputs(M, N, K, "int2", "zeros", seed=40 + seed)
+        cases.append((A, B, C0, DevMat(A), DevMat(B), DevMat(C0), torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    for _ in range(3):
+        for A, B, C0, dA, dB, dC, s in cases:
+            M, K = A.shape
+            binding.check(binding.gemm_f16_f32acc(M, B.shape[1], K, dA.ptr, dA.ld, dB.ptr, dB.ld, dC.ptr, dC.ld, s.cuda_stream))
+    torch.cuda.synchronize()
+    for A, B, C0, dA, dB, dC, s in cases:
+        Cref, _ = oracle_mod.gemm_f16(A, B, C0)
+        assert np.array_equal(dC.fetch(), oracle_mod.round_to_f32(3.0 * Cref))      # integer data: exact
+
+
+def test_under_hip_graph_capture(oracle_mod):
+    """The entry points only enqueue kernels (no allocation, no synchronisation,
+    no memset), so a call can be captured into a HIP graph; every replay, with
+    eager work and synchronisations in between, must equal the eager result."""
+    from gpu_util import DevMat
+    M, N, K = 1024, 1032, 520
+    A, B, C0 = wl.make_inputs(M, N, K, "int2", "zeros", seed=50)
+    dA, dB, dC = DevMat(A), DevMat(B), DevMat(C0)
+    Cref, _ = oracle_mod.gemm_f16(A, B, C0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                                  # warm-up outside capture, as torch asks
+        binding.check(binding.gemm_f16_f32acc(M, N, K, dA.ptr, dA.ld, dB.ptr, dB.ld, dC.ptr, dC.ld, side.cuda_stream))
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        rc = binding.gemm_f16_f32acc(M, N, K, dA.ptr, dA.ld, dB.ptr, dB.ld, dC.ptr, dC.ld,
+                                     torch.cuda.current_stream().cuda_stream)
+    assert rc == binding.OK
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.fetch(), oracle_mod.round_to_f32(1.0 * Cref))          # capture itself ran nothing
+    for rep in range(2, 5):
+        g.replay()
+        torch.cuda.synchronize()
+        scratch = torch.ones(1 << 20, device="cuda").sum().item()  # eager work between replays
+        assert scratch == float(1 << 20)
+        assert np.array_equal(dC.fetch(), oracle_mod.round_to_f32(float(rep) * Cref)), f"replay {rep - 1}"
