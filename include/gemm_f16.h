@@ -117,7 +117,11 @@ const char* gemm_strerror(int code);
 
 /*
  * Tile configuration report (the paper picks the best of several thread-block
- * and warp tile combinations per problem size: Evaluation section).
+ * and warp tile combinations per problem size: Evaluation section).  When the
+ * tile count of the largest tile does not fill the last round of workgroups
+ * on the device, a call may run as two launches on the caller's stream: whole
+ * rounds of the largest tile on the first rows of C, another configuration on
+ * the rest.
  */
 typedef struct gemm_f16_config {
     int32_t id;          /* index into the library's configuration table */
@@ -128,8 +132,10 @@ typedef struct gemm_f16_config {
     int32_t wave_m;      /* wavefront tile rows */
     int32_t wave_n;      /* wavefront tile columns */
     int32_t lds_bytes;   /* LDS bytes per workgroup */
-    int64_t grid;        /* workgroups launched for the queried problem */
-    char name[48];       /* short label, NUL-terminated */
+    int64_t grid;        /* workgroups launched for the queried problem (both launches of a split) */
+    int32_t split_rows;  /* 0, or: configuration `id` computes the first split_rows rows of C ... */
+    int32_t id2;         /* ... and configuration id2 the remaining rows in a second launch (-1: none) */
+    char name[48];       /* short label of configuration `id`, NUL-terminated */
 } gemm_f16_config;
 
 /*

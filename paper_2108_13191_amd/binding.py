@@ -23,7 +23,7 @@ class GemmConfig(ctypes.Structure):
     _fields_ = [("id", ctypes.c_int32), ("block_m", ctypes.c_int32), ("block_n", ctypes.c_int32),
                 ("block_k", ctypes.c_int32), ("waves", ctypes.c_int32), ("wave_m", ctypes.c_int32),
                 ("wave_n", ctypes.c_int32), ("lds_bytes", ctypes.c_int32), ("grid", ctypes.c_int64),
-                ("name", ctypes.c_char * 48)]
+                ("split_rows", ctypes.c_int32), ("id2", ctypes.c_int32), ("name", ctypes.c_char * 48)]
 
     def as_dict(self):
         d = {k: getattr(self, k) for k, _ in self._fields_}

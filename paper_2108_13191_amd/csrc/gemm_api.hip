@@ -47,42 +47,82 @@ bool aligned_for_tiled(int64_t N, int64_t K, const void* A, int64_t lda, const v
            lda <= (1 << 22) && ldb <= (1 << 22);
 }
 
-// Pick the configuration with the lowest estimated time.  The estimate is the
-// number of rounds the grid needs on 256 compute units times the work of one
-// tile, divided by a per-configuration efficiency measured on MI355X (large
-// tiles reuse operands better; small tiles fill the chip on small problems --
-// the trade-off the paper reports in section Mixed Precision Performance).
-int select_config(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb)
+// What a call runs: one configuration on all rows, or the 256 x 256 kernel on
+// the first rows1 rows and configuration id2 on the rest (second launch on the
+// same stream; the row ranges of C are disjoint).
+struct Plan { int id; int64_t rows1; int id2; };
+
+struct Cand { int id; double eff; int per_cu; };
+// ids: 3 = 256x256 (eight wavefronts, phase-alternating, 16x16x32 MFMA: measured
+// faster than the 32x32x16 form of the same kernel, id 2), 7 and 8 = its 192- and
+// 128-row forms (less operand reuse per tile, but e.g. 6144^3 is exactly three
+// rounds of 192x256 tiles instead of 2.25 of 256x256), 5 = 128x128, 6 = 64x64;
+// eff = measured throughput per unit of tile area relative to id 3.
+const Cand kCands[] = {{3, 1.0, 1}, {7, 0.87, 1}, {8, 0.78, 1}, {5, 0.7, 2}, {6, 0.4, 4}};
+
+// Estimated time of one launch in units of tile area: the rounds the grid needs
+// on 256 compute units times the work of one tile, divided by the
+// configuration's efficiency (large tiles reuse operands better; small tiles
+// fill the chip on small problems -- the trade-off the paper reports in
+// section Mixed Precision Performance).  A partial round costs a full one.
+double launch_cost(const Cand& c, int64_t M, int64_t N)
 {
-    if (!aligned_for_tiled(N, K, A, lda, B, ldb)) return 0;
-    if (g_forced >= 0 && g_forced < num_configs()) return g_forced;
-    struct Cand { int id; double eff; int per_cu; };
-    // ids: 3 = 256x256 (eight wavefronts, phase-alternating, 16x16x32 MFMA: measured
-    // faster than the 32x32x16 form of the same kernel, id 2), 7 and 8 = its 192- and
-    // 128-row forms (less operand reuse per tile, but e.g. 6144^3 is exactly three
-    // rounds of 192x256 tiles instead of 2.25 of 256x256), 5 = 128x128, 6 = 64x64
-    const Cand cands[] = {{3, 1.0, 1}, {7, 0.87, 1}, {8, 0.78, 1}, {5, 0.7, 2}, {6, 0.4, 4}};
+    const GemmConfigDesc* d = config(c.id);
+    const int64_t g = d->grid(M, N);
+    if (g < 0) return -1.0;
+    const int64_t slots = 256 * c.per_cu;
+    const double rounds = (double)((g + slots - 1) / slots);
+    return rounds * c.per_cu * (double)d->block_m * d->block_n / c.eff;
+}
+
+int best_single(int64_t M, int64_t N, double* cost_out)
+{
     int best = 3;
-    double best_cost = 0;
-    for (const Cand& c : cands) {
-        const GemmConfigDesc* d = config(c.id);
-        const int64_t g = d->grid(M, N);
-        if (g < 0) continue;
-        const double slots = 256.0 * c.per_cu;
-        const double rounds = (double)((g + (int64_t)slots - 1) / (int64_t)slots);
-        const double cost = rounds * c.per_cu * (double)d->block_m * d->block_n / c.eff;
-        if (best_cost == 0 || cost < best_cost) { best_cost = cost; best = c.id; }
+    double best_cost = -1.0;
+    for (const Cand& c : kCands) {
+        const double cost = launch_cost(c, M, N);
+        if (cost < 0) continue;
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = c.id; }
+    }
+    *cost_out = best_cost;
+    return best;
+}
+
+// Pick the plan with the lowest estimated time.  Besides the single launches,
+// the rows are cut once: whole rounds of 256 x 256 tiles first, and whatever
+// configuration suits the left-over rows best behind them -- 5120^3 is one full
+// round of 256 x 256 tiles plus one round of 192 x 256 tiles instead of two
+// rounds of which the second is 56 % full.
+Plan select_plan(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb)
+{
+    if (!aligned_for_tiled(N, K, A, lda, B, ldb)) return {0, M, -1};
+    if (g_forced >= 0 && g_forced < num_configs()) return {g_forced, M, -1};
+    double cost = 0;
+    Plan best = {best_single(M, N, &cost), M, -1};
+    const int64_t tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
+    if (tiles_n > 256 || tiles_m < 2 || cost < 0) return best;
+    const double second_launch = 1500.0;                  // drain and refill between the two launches
+    const int64_t total_rounds = (tiles_m * tiles_n + 255) / 256;
+    for (int64_t r = 1; r <= total_rounds; r++) {
+        const int64_t j = (r * 256) / tiles_n;             // tile rows that fit r rounds
+        if (j < 1 || j >= tiles_m) continue;
+        double rest = 0;
+        const int id2 = best_single(M - 256 * j, N, &rest);
+        const double first = (double)((j * tiles_n + 255) / 256) * 65536.0;
+        if (rest >= 0 && first + rest + second_launch < cost) { cost = first + rest + second_launch; best = {3, 256 * j, id2}; }
     }
     return best;
 }
 
-void fill_desc(int id, int64_t grid, gemm_f16_config* out)
+void fill_desc(int id, int64_t grid, gemm_f16_config* out, int64_t split_rows = 0, int id2 = -1)
 {
     const GemmConfigDesc* d = config(id);
     memset(out, 0, sizeof(*out));
     out->id = id; out->block_m = d->block_m; out->block_n = d->block_n; out->block_k = d->block_k;
     out->waves = d->waves; out->wave_m = d->wave_m; out->wave_n = d->wave_n; out->lds_bytes = d->lds_bytes;
     out->grid = grid;
+    out->split_rows = (int32_t)split_rows;
+    out->id2 = id2;
     strncpy(out->name, d->name, sizeof(out->name) - 1);
 }
 
@@ -106,10 +146,16 @@ int run(int c_is_f16, int64_t M, int64_t N, int64_t K, const void* A, int64_t ld
         a.c_is_f16 = c_is_f16; a.stream = (hipStream_t)stream;
         return config(0)->launch(a);
     }
-    a.M = M; a.N = N; a.K = K;
+    const Plan plan = select_plan(M, N, K, A, lda, B, ldb);
+    a.M = plan.rows1; a.N = N; a.K = K;
     a.A = (const half_t*)A; a.lda = lda; a.B = (const half_t*)B; a.ldb = ldb; a.C = C; a.ldc = ldc;
     a.c_is_f16 = c_is_f16; a.stream = (hipStream_t)stream;
-    return config(select_config(M, N, K, A, lda, B, ldb))->launch(a);
+    const int rc1 = config(plan.id)->launch(a);
+    if (rc1 != GEMM_F16_OK || plan.rows1 == M) return rc1;
+    a.M = M - plan.rows1;                                   // the left-over rows: A and C move down, B stays
+    a.A = (const half_t*)A + plan.rows1 * lda;
+    a.C = (char*)C + plan.rows1 * ldc * (c_is_f16 ? 2 : 4);
+    return config(plan.id2)->launch(a);
 }
 
 }  // namespace
@@ -166,10 +212,16 @@ int gemm_f16_query_config(int c_is_f16, int64_t M, int64_t N, int64_t K, const v
     const void* c = C ? C : (const void*)16;
     const int rc = check_args(c_is_f16, M, N, K, a, lda, b, ldb, c, ldc);
     if (rc != GEMM_F16_OK) return rc;
-    const int id = select_config(M, N, K, a, lda, b, ldb);
-    const int64_t g = (M == 0 || N == 0 || K == 0) ? 0 : config(id)->grid(M, N);
+    const Plan plan = select_plan(M, N, K, a, lda, b, ldb);
+    if (M == 0 || N == 0 || K == 0) { fill_desc(plan.id, 0, out); return GEMM_F16_OK; }
+    int64_t g = config(plan.id)->grid(plan.rows1, N);
     if (g < 0) return GEMM_F16_ERR_SIZE;
-    fill_desc(id, g, out);
+    if (plan.rows1 < M) {
+        const int64_t g2 = config(plan.id2)->grid(M - plan.rows1, N);
+        if (g2 < 0) return GEMM_F16_ERR_SIZE;
+        g += g2;
+    }
+    fill_desc(plan.id, g, out, plan.rows1 < M ? plan.rows1 : 0, plan.rows1 < M ? plan.id2 : -1);
     return GEMM_F16_OK;
 }
 

@@ -245,3 +245,18 @@ def test_under_hip_graph_capture(oracle_mod):
         scratch = torch.ones(1 << 20, device="cuda").sum().item()  # eager work between replays
         assert scratch == float(1 << 20)
         assert np.array_equal(dC.fetch(), oracle_mod.round_to_f32(float(rep) * Cref)), f"replay {rep - 1}"
+
+
+@pytest.mark.parametrize("mode", ["f32", "f16"])
+def test_row_split_plan(oracle_mod, mode):
+    """A problem the selector runs as two launches (whole rounds of 256 x 256 tiles
+    on the first rows, another configuration on the rest): every element against
+    the oracle, bit-exact on integer inputs, ragged last rows included."""
+    M, N, K = 4300, 4352, 192
+    q = binding.query_config(mode == "f16", M, N, K, 256, K, 256, N, 256, N)
+    assert 0 < q["split_rows"] < M and q["id2"] >= 0, q
+    A, B, C0 = wl.make_inputs(M, N, K, "int1", "zeros", seed=61, c_dtype=CDT[mode])
+    C0[:] = (np.arange(M)[:, None] + np.arange(N)[None, :]) % 5 - 2
+    _check(oracle_mod, A, B, C0, mode, exact=True, what=f"row split {q}")
+    A, B, C0 = wl.make_inputs(M, N, K, "uniform", "uniform", seed=62, c_dtype=CDT[mode])
+    _check(oracle_mod, A, B, C0, mode, what=f"row split {q}")
