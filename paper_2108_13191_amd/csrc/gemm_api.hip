@@ -103,7 +103,7 @@ Plan select_plan(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, co
     if (tiles_n > 256 || tiles_m < 2 || cost < 0) return best;
     const double second_launch = 1500.0;                  // drain and refill between the two launches
     const int64_t total_rounds = (tiles_m * tiles_n + 255) / 256;
-    for (int64_t r = 1; r <= total_rounds; r++) {
+    for (int64_t r = total_rounds > 4 ? total_rounds - 3 : 1; r <= total_rounds; r++) {   // the cut is near the end
         const int64_t j = (r * 256) / tiles_n;             // tile rows that fit r rounds
         if (j < 1 || j >= tiles_m) continue;
         double rest = 0;
