@@ -37,8 +37,8 @@ def kernel_symbol(tile_name, mode, K=0):
     ct = "float" if mode == "f32" else "_Float16"
     if tile_name.startswith("pp256"):
         mi = 16 if "mi16" in tile_name else 32
-        bm = int(tile_name[2:5])
-        return f"gemm_pp256_kernel<{ct}, {mi}, {'true' if K % 64 else 'false'}, {bm}>"
+        bm, bn = int(tile_name[2:5]), int(tile_name[6:9])
+        return f"gemm_pp256_kernel<{ct}, {mi}, {'true' if K % 64 else 'false'}, {bm}, {bn}>"
     if tile_name.startswith("w4_"):
         return f"gemm_w4_kernel<{ct}>"
     if tile_name.startswith("generic"):

@@ -10,8 +10,8 @@ namespace {
 // Configuration table: entry 0 is the any-shape kernel, entry 1 the 256 x 256
 // four-wavefront kernel, entries 2 and 3 the 256 x 256 phase-alternating
 // eight-wavefront kernel on 32x32x16 and on 16x16x32 MFMAs, then the generic
-// double-buffered tiles, then the 192- and 128-row forms of entry 3.
-int num_configs() { return 4 + tiled_num_configs() + 2; }
+// double-buffered tiles, then the 192 x 256, 128 x 256 and 128 x 128 forms of entry 3.
+int num_configs() { return 4 + tiled_num_configs() + 3; }
 
 const GemmConfigDesc kGeneric = {
     "generic64x64x32", 64, 64, 32, 4, 32, 32, 2 * 64 * (32 + 8) * 2,
@@ -20,8 +20,8 @@ const GemmConfigDesc kGeneric = {
 const GemmConfigDesc* config(int id)
 {
     const int nt = tiled_num_configs();
-    if (id >= 4 + nt) return pingpong16_config(id == 4 + nt ? 192 : 128);
-    return id == 0 ? &kGeneric : id == 1 ? w4_config() : id == 2 ? pingpong_config() : id == 3 ? pingpong16_config(256) : tiled_config(id - 4);
+    if (id >= 4 + nt) return id == 4 + nt ? pingpong16_config(192, 256) : id == 5 + nt ? pingpong16_config(128, 256) : pingpong16_config(128, 128);
+    return id == 0 ? &kGeneric : id == 1 ? w4_config() : id == 2 ? pingpong_config() : id == 3 ? pingpong16_config(256, 256) : tiled_config(id - 4);
 }
 
 int g_forced = -1;
@@ -56,31 +56,42 @@ struct Cand { int id; double eff; int per_cu; };
 // ids: 3 = 256x256 (eight wavefronts, phase-alternating, 16x16x32 MFMA: measured
 // faster than the 32x32x16 form of the same kernel, id 2), 7 and 8 = its 192- and
 // 128-row forms (less operand reuse per tile, but e.g. 6144^3 is exactly three
-// rounds of 192x256 tiles instead of 2.25 of 256x256), 5 = 128x128, 6 = 64x64;
-// eff = measured throughput per unit of tile area relative to id 3.
-const Cand kCands[] = {{3, 1.0, 1}, {7, 0.87, 1}, {8, 0.78, 1}, {5, 0.7, 2}, {6, 0.4, 4}};
+// rounds of 192x256 tiles instead of 2.25 of 256x256), 9 = its 128x128 form (two
+// workgroups per compute unit, which hide each other's prologue and epilogue:
+// the choice for problems of a few hundred tiles), 5 = 128x128 and 6 = 64x64 of
+// the plain double-buffered kernel; eff = measured throughput per unit of tile
+// area relative to id 3.
+const Cand kCands[] = {{3, 1.0, 1}, {7, 0.87, 1}, {8, 0.78, 1}, {9, 0.9, 2}, {5, 0.7, 2}, {6, 0.4, 4}};
 
 // Estimated time of one launch in units of tile area: the rounds the grid needs
 // on 256 compute units times the work of one tile, divided by the
 // configuration's efficiency (large tiles reuse operands better; small tiles
 // fill the chip on small problems -- the trade-off the paper reports in
-// section Mixed Precision Performance).  A partial round costs a full one.
-double launch_cost(const Cand& c, int64_t M, int64_t N)
+// section Mixed Precision Performance).  A partial round costs a full one,
+// except that workgroups which would share a compute unit and do not have to
+// (the last round has fewer than 256 x per_cu of them) run somewhat faster.
+// The 128 x 128 form's two workgroups per compute unit hide each other's
+// prologue and epilogue, which counts for more the shorter the k loop is.
+double launch_cost(const Cand& c, int64_t M, int64_t N, int64_t K)
 {
     const GemmConfigDesc* d = config(c.id);
     const int64_t g = d->grid(M, N);
     if (g < 0) return -1.0;
+    double eff = c.eff;
+    if (c.id == 9) { eff = 0.78 + 0.2 * (K < 1024 ? 1.0 : 1024.0 / (double)K); if (eff > 0.92) eff = 0.92; }
     const int64_t slots = 256 * c.per_cu;
-    const double rounds = (double)((g + slots - 1) / slots);
-    return rounds * c.per_cu * (double)d->block_m * d->block_n / c.eff;
+    const int64_t full = g / slots, left = g % slots;
+    const double sharing = (double)((left + 255) / 256);                       // workgroups per compute unit in the last round
+    const double last = left ? (0.5 + 0.5 * sharing / c.per_cu) * c.per_cu : 0.0;
+    return ((double)full * c.per_cu + last) * (double)d->block_m * d->block_n / eff;
 }
 
-int best_single(int64_t M, int64_t N, double* cost_out)
+int best_single(int64_t M, int64_t N, int64_t K, double* cost_out)
 {
     int best = 3;
     double best_cost = -1.0;
     for (const Cand& c : kCands) {
-        const double cost = launch_cost(c, M, N);
+        const double cost = launch_cost(c, M, N, K);
         if (cost < 0) continue;
         if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = c.id; }
     }
@@ -98,16 +109,16 @@ Plan select_plan(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, co
     if (!aligned_for_tiled(N, K, A, lda, B, ldb)) return {0, M, -1};
     if (g_forced >= 0 && g_forced < num_configs()) return {g_forced, M, -1};
     double cost = 0;
-    Plan best = {best_single(M, N, &cost), M, -1};
+    Plan best = {best_single(M, N, K, &cost), M, -1};
     const int64_t tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
     if (tiles_n > 256 || tiles_m < 2 || cost < 0) return best;
-    const double second_launch = 1500.0;                  // drain and refill between the two launches
+    const double second_launch = 3000.0;                  // drain and refill between the two launches
     const int64_t total_rounds = (tiles_m * tiles_n + 255) / 256;
     for (int64_t r = total_rounds > 4 ? total_rounds - 3 : 1; r <= total_rounds; r++) {   // the cut is near the end
         const int64_t j = (r * 256) / tiles_n;             // tile rows that fit r rounds
         if (j < 1 || j >= tiles_m) continue;
         double rest = 0;
-        const int id2 = best_single(M - 256 * j, N, &rest);
+        const int id2 = best_single(M - 256 * j, N, K, &rest);
         const double first = (double)((j * tiles_n + 255) / 256) * 65536.0;
         if (rest >= 0 && first + rest + second_launch < cost) { cost = first + rest + second_launch; best = {3, 256 * j, id2}; }
     }

@@ -46,7 +46,7 @@ const GemmConfigDesc* tiled_config(int i);
 
 // gemm_pingpong.hip
 const GemmConfigDesc* pingpong_config();
-const GemmConfigDesc* pingpong16_config(int block_m);   // 256, 192 or 128 rows per tile
+const GemmConfigDesc* pingpong16_config(int block_m, int block_n);   // 256x256, 192x256, 128x256 or 128x128
 
 // gemm_w4.hip
 const GemmConfigDesc* w4_config();

@@ -60,10 +60,7 @@ namespace {
 
 using namespace gemm_dev;
 
-constexpr int PBN = 256;
-constexpr int B_BUF = BK * PBN * 2;          // 32 KB
 constexpr int A_REGION = 0;                  // two A buffers, then three B buffers
-constexpr int B_ROW = PBN * 2;               // bytes per k row of a B stage
 
 __device__ __forceinline__ void phase_barrier()
 {
@@ -91,11 +88,16 @@ template <int V> struct IntTag { static constexpr int value = V; };
 
 // BM = rows of the workgroup tile: 256, or 192 / 128 for problems whose tile count
 // fills the compute units better that way (the wavefront tile is then 96 x 64 /
-// 64 x 64; everything else is unchanged).
-template <typename CT, int MI, bool TAIL, int BM>
+// 64 x 64; everything else is unchanged).  BN = its columns: 256, or 128 (wavefront
+// tile 32 columns wide) for the small-problem form 128 x 128.
+template <typename CT, int MI, bool TAIL, int BM, int BN>
 __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
 {
     constexpr int HM = BM / 2;                       // rows per wavefront group
+    constexpr int WN = BN / 4;                       // columns per wavefront
+    constexpr int B_BUF = BK * BN * 2;               // 32 KB for BN = 256
+    constexpr int B_ROW = BN * 2;                    // bytes per k row of a B stage
+    constexpr int TB = BN / 64;                      // copies per wavefront and B half
     constexpr int A_BUF = BM * BK * 2;               // 32 KB for BM = 256
     constexpr int B_REGION = 2 * A_BUF;
     constexpr int PP_LDS = 2 * A_BUF + 3 * B_BUF;    // 160 KB for BM = 256
@@ -111,8 +113,8 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
 
     int tile_m, tile_n;
     tile_of_block(p, blockIdx.x, tile_m, tile_n);
-    const int m0 = tile_m * BM, n0 = tile_n * PBN;
-    const bool edge = (m0 + BM > p.M) || (n0 + PBN > p.N);
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const bool edge = (m0 + BM > p.M) || (n0 + BN > p.N);
 
     const int kt_full = p.K / BK;
     const int KT = (p.K + BK - 1) / BK;
@@ -130,20 +132,21 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
         row = (m0 + row < p.M) ? row : p.M - 1 - m0;                 // clamp: loaded, never stored
         return ((uint32_t)row * (uint32_t)p.lda + 8 * a_chunk) * 2;
     };
-    // B half (32 k rows x 512 B = 16 KB) = 16 copies of 2 k rows; copy q = wn + 4t.
-    // Lane i writes (k row 2q + i/32, chunk position i%32), which must hold logical
-    // chunk position ^ swz(k row), swz = 4*(row%4) + 2*((row/8)%2): the row%4 term
-    // spreads the four k rows of one transposing read over the banks, the
-    // (row/8)%2 term those of the 16-lane blocks that read k and k+8 together
-    // (16x16x32 operands).  (row/8)%2 = t%2 here.
-    const int b_krow_in_copy = lane >> 5;
+    // B half (32 k rows x B_ROW bytes) = 4 * TB wave-wide copies of 1 KB = RPC k rows
+    // each (2 for BN = 256, 4 for BN = 128); copy q = wn + 4t.  Lane i writes (k row
+    // RPC*q + i/CPR, chunk position i%CPR), which must hold logical chunk position
+    // ^ swz(k row), swz = 4*(row%4) + 2*((row/8)%2): the row%4 term spreads the
+    // four k rows of one transposing read over the banks, the (row/8)%2 term those
+    // of the 16-lane blocks that read k and k+8 together (16x16x32 operands).
+    constexpr int CPR = B_ROW / 16, RPC = 64 / CPR;                  // chunks per k row, k rows per copy
+    auto b_krow = [&](int t) -> int { return RPC * (wn + 4 * t) + lane / CPR; };   // within the half
     auto b_offset = [&](int t) -> uint32_t {                          // relative to the half's first k row
-        const int swz = (((2 * wn + b_krow_in_copy) & 3) << 2) | ((t & 1) << 1);
-        int col = 8 * ((lane & 31) ^ swz);
+        const int krow = b_krow(t);
+        const int swz = ((krow & 3) << 2) | (((krow >> 3) & 1) << 1);
+        int col = 8 * ((lane % CPR) ^ swz);
         if (n0 + col + 8 > p.N) col = 0;                              // clamp: loaded, never stored
-        return ((uint32_t)(2 * (wn + 4 * t) + b_krow_in_copy) * (uint32_t)p.ldb + col) * 2;
+        return ((uint32_t)krow * (uint32_t)p.ldb + col) * 2;
     };
-
     // Copy t (of 4 per wavefront) of one A half of k step s into A buffer s%2;
     // `off` = the caller's 4 lane offsets.  A whole k step goes global -> LDS
     // directly; the k tail (the last k step when K is not a multiple of 64) goes
@@ -169,7 +172,7 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
         } else {
             const int kvalid = p.K - s * BK - half * 32;               // valid k rows of this half (may be <= 0)
             uintx4 v = {0u, 0u, 0u, 0u};
-            if (2 * (wn + 4 * t) + b_krow_in_copy < kvalid) v = *reinterpret_cast<const uintx4*>((const char*)src + off[t]);
+            if (b_krow(t) < kvalid) v = *reinterpret_cast<const uintx4*>((const char*)src + off[t]);
             *(__attribute__((address_space(3))) uintx4*)(uintptr_t)(dst + 16 * lane) = v;
         }
     };
@@ -178,7 +181,7 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     // in the A rows it reads itself and one k half of B for both groups.
     uint32_t a_off[4], b_off[4];
 #pragma unroll
-    for (int t = 0; t < 4; t++) { a_off[t] = t < TA ? a_offset(grp, t) : 0u; b_off[t] = b_offset(t); }
+    for (int t = 0; t < 4; t++) { a_off[t] = t < TA ? a_offset(grp, t) : 0u; b_off[t] = t < TB ? b_offset(t) : 0u; }
 
     // ---- prologue: k steps 0 and 1 ---------------------------------------------
 #pragma unroll
@@ -186,10 +189,10 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
         if (s < KT) {
             if (!TAIL || s < kt_full) {
 #pragma unroll
-                for (int t = 0; t < 4; t++) { if (t < TA) copy_a_part(s, grp, a_off, t, BoolTag<true>{}); copy_b_part(s, grp, b_off, t, BoolTag<true>{}); }
+                for (int t = 0; t < 4; t++) { if (t < TA) copy_a_part(s, grp, a_off, t, BoolTag<true>{}); if (t < TB) copy_b_part(s, grp, b_off, t, BoolTag<true>{}); }
             } else {
 #pragma unroll
-                for (int t = 0; t < 4; t++) { if (t < TA) copy_a_part(s, grp, a_off, t, BoolTag<false>{}); copy_b_part(s, grp, b_off, t, BoolTag<false>{}); }
+                for (int t = 0; t < 4; t++) { if (t < TA) copy_a_part(s, grp, a_off, t, BoolTag<false>{}); if (t < TB) copy_b_part(s, grp, b_off, t, BoolTag<false>{}); }
             }
         }
 
@@ -200,7 +203,7 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     // is row l%32, column 8*(i/4) + 4*(l/32) + i%4 -- 4 consecutive columns per
     // register group, which the epilogue moves 16 bytes at a time.  (16 x 16
     // blocks: register r of lane l is row l%16, column 4*(l/16) + r.)
-    constexpr int FM = HM / MI, FN = 64 / MI;        // accumulator blocks per wavefront tile
+    constexpr int FM = HM / MI, FN = WN / MI;        // accumulator blocks per wavefront tile
     typedef typename AccBlock<MI>::type acc_t;       // 16 (MI = 32) or 4 (MI = 16) registers
     acc_t acc[FM][FN];
 #pragma unroll
@@ -211,7 +214,7 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
             for (int i = 0; i < MI * MI / 64; i++) acc[fm][fn][i] = 0.0f;
     CT* const Cbase = (CT*)p.C;
     const int crow0 = m0 + grp * HM;
-    const int ccol0 = n0 + wn * 64;
+    const int ccol0 = n0 + wn * WN;
 
     // ---- fragment read addresses ----------------------------------------------
     // MI = 32: A operand lane l holds tile row l%32 of its block, k = 8*(l/32)..+7 of
@@ -240,7 +243,7 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
         const int swz = ((krow & 3) << 2) | (((krow >> 3) & 1) << 1);                    // unchanged by +4, +16, +32
 #pragma unroll
         for (int fn = 0; fn < FN; fn++) {
-            const int col = wn * 64 + fn * MI + ((MI == 32) ? 16 * (blk & 1) : 0) + 4 * (j & 3);   // first of 4 columns
+            const int col = wn * WN + fn * MI + ((MI == 32) ? 16 * (blk & 1) : 0) + 4 * (j & 3);   // first of 4 columns
             b_rd[fn] = smem_base + B_REGION + (uint32_t)krow * B_ROW + (uint32_t)(((col >> 3) ^ swz) * 16 + 2 * (col & 7));
         }
     }
@@ -282,6 +285,8 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     // that the barrier that follows publishes them.
     constexpr int NMFMA = (NSL / 2) * FM * FN;
     constexpr int NPRE = (sizeof(CT) == 2) ? 2 : 1;     // slabs of 32 C rows requested before the last two k steps
+    constexpr int LPR = WN / 4;                         // epilogue: lanes per row segment (4 columns each),
+    constexpr int RPP = 64 / LPR, PASSES = 32 / RPP;    // rows per pass, passes per slab of 32 rows
     // copy_tag: 0 no copies (last two k steps), 1 k step k + 2 is a whole one,
     // 2 it is the k tail
     auto multiply_phase = [&](int k, int h, auto copy_tag) {
@@ -299,22 +304,19 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
                     const int idx = (s * FM + fm) * FN + fn;
                     if (COPY && idx % (NMFMA / 4) == NMFMA / 8 - 1) {
                         __builtin_amdgcn_sched_barrier(0);
-                        if (h == 0)                       copy_b_part(k + 2, grp, b_off, idx / (NMFMA / 4), whole_t{});
-                        else if (idx / (NMFMA / 4) < TA)  copy_a_part(k + 2, grp, a_off, idx / (NMFMA / 4), whole_t{});
+                        if (h == 0) { if (idx / (NMFMA / 4) < TB) copy_b_part(k + 2, grp, b_off, idx / (NMFMA / 4), whole_t{}); }
+                        else        { if (idx / (NMFMA / 4) < TA) copy_a_part(k + 2, grp, a_off, idx / (NMFMA / 4), whole_t{}); }
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
         if (h == 1) {
             __builtin_amdgcn_sched_barrier(0);
             if (whole_t::value) {
-                if constexpr (TA == 4)      asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-                else if constexpr (TA == 3) asm volatile("s_waitcnt vmcnt(7)" ::: "memory");
-                else                        asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+                asm volatile("s_waitcnt vmcnt(%0)" :: "n"(TA + TB) : "memory");      // this k step's copies may be outstanding
             }
             else if constexpr (decltype(copy_tag)::value == 0) {
                 // the last two k steps: only the early C loads (8 per slab) may be outstanding
-                if constexpr (NPRE == 2) asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
-                else                     asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+                asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" :: "n"(NPRE * PASSES) : "memory");
             } else {
                 asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
             }
@@ -335,9 +337,7 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     // behind it, completing in order) may still be on their way -- the wait at
     // the end of k step 0 covers them
     if (1 < kt_full) {
-        if constexpr (TA == 4)      asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        else if constexpr (TA == 3) asm volatile("s_waitcnt vmcnt(7)" ::: "memory");
-        else                        asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+        asm volatile("s_waitcnt vmcnt(%0)" :: "n"(TA + TB) : "memory");
     } else {
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     }
@@ -358,12 +358,12 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     // k steps are multiplied (loads complete in order: the waits of those k steps
     // leave exactly these loads outstanding).
     typedef typename CVec4<CT>::type ctx4;
-    constexpr int PITCH = 272;
+    constexpr int PITCH = WN * 4 + 16;                       // 272 B for 64 columns
     const uint32_t tbuf = smem_base + (uint32_t)wave * (32u * PITCH);
     // where this lane's 4 consecutive columns of a block go: row l%MI, column 4*(l/MI) (+ block offsets)
     const uint32_t w_addr = tbuf + (uint32_t)(lane & (MI - 1)) * PITCH + (uint32_t)(lane / MI) * 16;
-    const uint32_t r_addr = tbuf + (uint32_t)(lane >> 4) * PITCH + (uint32_t)(lane & 15) * 16;
-    const int orow = lane >> 4, ocol = 4 * (lane & 15);       // this lane's row (of 4) and column in a pass
+    const uint32_t r_addr = tbuf + (uint32_t)(lane / LPR) * PITCH + (uint32_t)(lane % LPR) * 16;
+    const int orow = lane / LPR, ocol = 4 * (lane % LPR);     // this lane's row (of RPP) and column in a pass
     const bool col_ok = !edge || (ccol0 + ocol < p.N);         // N is a multiple of 8: all 4 columns or none
     CT* const cptr = Cbase + (int64_t)(crow0 + orow) * p.ldc + ccol0 + ocol;
     float bias4[4] = {0.0f, 0.0f, 0.0f, 0.0f};              // fused epilogue: this lane's 4 columns of the bias
@@ -371,13 +371,13 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
 #pragma unroll
         for (int e = 0; e < 4; e++) bias4[e] = (float)reinterpret_cast<const CT*>(p.bias)[ccol0 + ocol + e];
     }
-    ctx4 cin[2][8];
-    auto fetch = [&](int fm, ctx4 (&dst)[8]) {
+    ctx4 cin[2][PASSES];
+    auto fetch = [&](int fm, ctx4 (&dst)[PASSES]) {
 #pragma unroll
-        for (int ps = 0; ps < 8; ps++) {
-            const bool ok = col_ok && (!edge || (crow0 + fm * 32 + 4 * ps + orow < p.M));
+        for (int ps = 0; ps < PASSES; ps++) {
+            const bool ok = col_ok && (!edge || (crow0 + fm * 32 + RPP * ps + orow < p.M));
             // a group outside C reads this lane's first (valid or clamped) group of the tile instead
-            const CT* src = ok ? cptr + (int64_t)(fm * 32 + 4 * ps) * p.ldc : Cbase + (int64_t)m0 * p.ldc + n0;
+            const CT* src = ok ? cptr + (int64_t)(fm * 32 + RPP * ps) * p.ldc : Cbase + (int64_t)m0 * p.ldc + n0;
             dst[ps] = *reinterpret_cast<const ctx4*>(src);
         }
     };
@@ -399,7 +399,7 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
             if (fm + 1 < HM / 32 && fm + 1 >= NPRE) fetch(fm + 1, cin[(fm + 1) & 1]);
             if constexpr (MI == 32) {
 #pragma unroll
-                for (int fn = 0; fn < 2; fn++)
+                for (int fn = 0; fn < FN; fn++)
 #pragma unroll
                     for (int g = 0; g < 4; g++) {
                         const floatx4 v = {acc[fm][fn][4 * g], acc[fm][fn][4 * g + 1], acc[fm][fn][4 * g + 2], acc[fm][fn][4 * g + 3]};
@@ -409,65 +409,71 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
 #pragma unroll
                 for (int r = 0; r < 2; r++)
 #pragma unroll
-                    for (int fn = 0; fn < 4; fn++)
+                    for (int fn = 0; fn < FN; fn++)
                         *(__attribute__((address_space(3))) floatx4*)(uintptr_t)(w_addr + r * 16 * PITCH + fn * 16 * 4) = acc[2 * fm + r][fn];
             }
 #pragma unroll
-            for (int ps = 0; ps < 8; ps++) {
-                const floatx4 s4 = *(__attribute__((address_space(3))) const floatx4*)(uintptr_t)(r_addr + 4 * ps * PITCH);
+            for (int ps = 0; ps < PASSES; ps++) {
+                const floatx4 s4 = *(__attribute__((address_space(3))) const floatx4*)(uintptr_t)(r_addr + RPP * ps * PITCH);
                 const ctx4 c4 = cin[fm & 1][ps];
                 ctx4 o;
 #pragma unroll
                 for (int e = 0; e < 4; e++) o[e] = (CT)epilogue_value(s4[e] + (float)c4[e], bias4[e], p.relu);      // f16: one rounding, to nearest even
-                if (col_ok && (!edge || (crow0 + fm * 32 + 4 * ps + orow < p.M)))
-                    *reinterpret_cast<ctx4*>(cptr + (int64_t)(fm * 32 + 4 * ps) * p.ldc) = o;
+                if (col_ok && (!edge || (crow0 + fm * 32 + RPP * ps + orow < p.M)))
+                    *reinterpret_cast<ctx4*>(cptr + (int64_t)(fm * 32 + RPP * ps) * p.ldc) = o;
             }
         }
     }
 }
 
-template <int BM>
+template <int BM, int BN>
 int64_t grid_pp(int64_t M, int64_t N)
 {
-    const int64_t tm = (M + BM - 1) / BM, tn = (N + PBN - 1) / PBN;
+    const int64_t tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
     if (tm > 0 && tn > INT32_MAX / tm) return -1;
     return tm * tn;
 }
 
-template <int MI, int BM>
+template <int MI, int BM, int BN>
 int launch_pp(const GemmArgs& a)
 {
-    const int64_t g = grid_pp<BM>(a.M, a.N);
+    const int64_t g = grid_pp<BM, BN>(a.M, a.N);
     if (g < 0) return GEMM_F16_ERR_SIZE;
     TiledParams p;
     p.M = (int)a.M; p.N = (int)a.N; p.K = (int)a.K;
     p.A = a.A; p.lda = a.lda; p.B = a.B; p.ldb = a.ldb; p.C = a.C; p.ldc = a.ldc;
     p.bias = a.bias; p.relu = a.relu;
     p.tiles_m = (int)((a.M + BM - 1) / BM);
-    p.tiles_n = (int)((a.N + PBN - 1) / PBN);
+    p.tiles_n = (int)((a.N + BN - 1) / BN);
     p.group_m = 8 < p.tiles_m ? 8 : p.tiles_m;     // an XCD's 32 concurrent tiles form an 8 x 4 block of C
     const bool tail = (a.K % BK) != 0;
     if (a.c_is_f16) {
-        if (tail) hipLaunchKernelGGL((gemm_pp256_kernel<half_t, MI, true, BM>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
-        else      hipLaunchKernelGGL((gemm_pp256_kernel<half_t, MI, false, BM>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
+        if (tail) hipLaunchKernelGGL((gemm_pp256_kernel<half_t, MI, true, BM, BN>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
+        else      hipLaunchKernelGGL((gemm_pp256_kernel<half_t, MI, false, BM, BN>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
     } else {
-        if (tail) hipLaunchKernelGGL((gemm_pp256_kernel<float, MI, true, BM>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
-        else      hipLaunchKernelGGL((gemm_pp256_kernel<float, MI, false, BM>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
+        if (tail) hipLaunchKernelGGL((gemm_pp256_kernel<float, MI, true, BM, BN>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
+        else      hipLaunchKernelGGL((gemm_pp256_kernel<float, MI, false, BM, BN>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
     }
     return hipGetLastError() == hipSuccess ? GEMM_F16_OK : GEMM_F16_ERR_LAUNCH;
 }
 
-constexpr int lds_pp(int bm) { return 2 * bm * BK * 2 + 3 * B_BUF; }
+constexpr int lds_pp(int bm, int bn) { return 2 * bm * BK * 2 + 3 * BK * bn * 2; }
 const GemmConfigDesc kPingPong = {
-    "pp256x256x64_w2x4", 256, PBN, BK, 8, 128, 64, lds_pp(256), true, launch_pp<32, 256>, grid_pp<256>};
+    "pp256x256x64_w2x4", 256, 256, BK, 8, 128, 64, lds_pp(256, 256), true, launch_pp<32, 256, 256>, grid_pp<256, 256>};
 const GemmConfigDesc kPingPong16 = {
-    "pp256x256x64_w2x4_mi16", 256, PBN, BK, 8, 128, 64, lds_pp(256), true, launch_pp<16, 256>, grid_pp<256>};
+    "pp256x256x64_w2x4_mi16", 256, 256, BK, 8, 128, 64, lds_pp(256, 256), true, launch_pp<16, 256, 256>, grid_pp<256, 256>};
 const GemmConfigDesc kPingPong16_192 = {
-    "pp192x256x64_w2x4_mi16", 192, PBN, BK, 8, 96, 64, lds_pp(192), true, launch_pp<16, 192>, grid_pp<192>};
+    "pp192x256x64_w2x4_mi16", 192, 256, BK, 8, 96, 64, lds_pp(192, 256), true, launch_pp<16, 192, 256>, grid_pp<192, 256>};
 const GemmConfigDesc kPingPong16_128 = {
-    "pp128x256x64_w2x4_mi16", 128, PBN, BK, 8, 64, 64, lds_pp(128), true, launch_pp<16, 128>, grid_pp<128>};
+    "pp128x256x64_w2x4_mi16", 128, 256, BK, 8, 64, 64, lds_pp(128, 256), true, launch_pp<16, 128, 256>, grid_pp<128, 256>};
+const GemmConfigDesc kPingPong16_128x128 = {
+    "pp128x128x64_w2x4_mi16", 128, 128, BK, 8, 64, 32, lds_pp(128, 128), true, launch_pp<16, 128, 128>, grid_pp<128, 128>};
 
 }  // namespace
 
 const GemmConfigDesc* pingpong_config() { return &kPingPong; }
-const GemmConfigDesc* pingpong16_config(int bm) { return bm == 128 ? &kPingPong16_128 : bm == 192 ? &kPingPong16_192 : &kPingPong16; }
+const GemmConfigDesc* pingpong16_config(int bm, int bn)
+{
+    if (bn == 128) return &kPingPong16_128x128;
+    return bm == 128 ? &kPingPong16_128 : bm == 192 ? &kPingPong16_192 : &kPingPong16;
+}
