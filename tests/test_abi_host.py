@@ -83,3 +83,38 @@ def test_config_table_and_selection(lib):
     assert binding.force_config(0) == 0
     assert binding.query_config(0, 8192, 8192, 8192, 16, 8192, 16, 8192, 16, 8192)["id"] == 0
     binding.force_config(-1)
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/gemm_f16.h compiles as C99 on its own, and a C program that calls
+    the host-only entry points links against the library and runs (no GPU)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    hdr = os.path.join(root, "include", "gemm_f16.h")
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-x", "c", hdr], check=True)
+    src = tmp_path / "use.c"
+    src.write_text('''
+#include <stdio.h>
+#include <string.h>
+#include "gemm_f16.h"
+int main(void) {
+    gemm_f16_config c;
+    if (gemm_f16_num_configs() < 1) return 1;
+    if (gemm_f16_describe_config(0, &c) != GEMM_F16_OK || strlen(c.name) == 0) return 2;
+    if (gemm_f16_query_config(0, 8192, 8192, 8192, (void*)256, 8192, (void*)256, 8192, (void*)256, 8192, &c) != GEMM_F16_OK) return 3;
+    if (c.block_m != 256 || c.grid != 1024) return 4;
+    if (gemm_f16_f32acc(-1, 1, 1, 0, 1, 0, 1, 0, 1, 0) != GEMM_F16_ERR_SIZE) return 5;
+    if (gemm_f16_f32acc_bias_act(4, 4, 4, (void*)256, 4, (void*)256, 4, (float*)256, 4, 0, 9, 0) != GEMM_F16_ERR_CONFIG) return 6;
+    printf("%s\\n", gemm_strerror(GEMM_F16_ERR_PITCH));
+    return 0;
+}
+''')
+    exe = tmp_path / "use"
+    libdir = os.path.join(root, "paper_2108_13191_amd")
+    subprocess.run(["gcc", "-std=c99", "-I", os.path.join(root, "include"), str(src), "-o", str(exe),
+                    "-L", libdir, "-lgemm_f16", f"-Wl,-rpath,{libdir}"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True)
+    assert "leading dimension" in out.stdout
