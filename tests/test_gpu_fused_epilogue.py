@@ -131,3 +131,14 @@ def test_errors():
     binding.force_config(W4)
     bias = np.ones(64, np.float32)
     run_fused(A, B, C0, bias, binding.ACT_NONE, "f32", expect=binding.ERR_CONFIG)   # comparison kernel: no fused epilogue
+
+
+def test_fused_epilogue_on_a_row_split_plan(oracle_mod):
+    """Both launches of a split plan apply the same bias and activation."""
+    M, N, K = 4300, 4352, 192
+    q = binding.query_config(False, M, N, K, 256, K, 256, N, 256, N)
+    assert 0 < q["split_rows"] < M
+    A, B, C0 = wl.make_inputs(M, N, K, "int1", "zeros", seed=71)
+    C0[:] = (np.arange(M)[:, None] * 3 + np.arange(N)[None, :]) % 7 - 3
+    bias = (np.arange(N) % 13 - 6).astype(np.float32)
+    check(oracle_mod, A, B, C0, bias, binding.ACT_RELU, "f32", exact=True, what="fused + row split")
