@@ -24,6 +24,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_F16_MFMA_TFLOPS = 2516.6      # 256 CU x 4096 flop/clk/CU x 2.4 GHz, dense
+ROTATE_BELOW_BYTES = 512 << 20   # operands + C of one call; the last-level cache holds 256 MB
 PEAK_HBM_GBS = 8000.0
 
 
@@ -35,9 +36,14 @@ def algorithmic_bytes(M, N, K, c_bytes):
 def kernel_symbol(tile_name, mode, K=0):
     """Name of the kernel as it shows in a rocprofv3 kernel trace."""
     ct = "float" if mode == "f32" else "_Float16"
-    if tile_name.startswith("pp256"):
+    if tile_name.startswith("pp"):
         mi = 16 if "mi16" in tile_name else 32
         bm, bn = int(tile_name[2:5]), int(tile_name[6:9])
+        tail = "true" if K % 64 else "false"
+        if tile_name.endswith("_chain"):
+            return f"gemm_pp256_persistent_kernel<{ct}, {mi}, {tail}>"
+        if tile_name.endswith("_stag"):
+            return f"gemm_pp_mixed_kernel<{ct}, {mi}, {tail}>"
         return f"gemm_pp256_kernel<{ct}, {mi}, {'true' if K % 64 else 'false'}, {bm}, {bn}>"
     if tile_name.startswith("w4_"):
         return f"gemm_w4_kernel<{ct}>"
@@ -60,26 +66,40 @@ def measured_traffic(tile_name, workload, mode):
     return None
 
 
-def time_gemm(binding, torch, mode, M, N, K, dA, dB, dC, steps, warmup):
-    """Return (ms per step over the timed region, list of per-launch ms)."""
+def time_gemm(binding, torch, mode, M, N, K, sets, steps, warmup):
+    """Time `steps` launches; launch i works on sets[i % len(sets)] (one set: every
+    launch re-reads the same operands, which the 256 MB last-level cache may still
+    hold; several sets larger than that cache in total: every launch finds its
+    operands in HBM only).  Return (ms per step, list of per-launch ms, host ms)."""
     fn = binding.gemm_f16_f32acc if mode == "f32" else binding.gemm_f16_f16acc
     stream = torch.cuda.current_stream()
     sp = stream.cuda_stream
+    dA, dB, dC = sets[0]
     lda, ldb, ldc = dA.stride(0), dB.stride(0), dC.stride(0)
-    for _ in range(warmup):
-        binding.check(fn(M, N, K, dA, lda, dB, ldb, dC, ldc, sp))
+    R = len(sets)
+    for i in range(warmup):
+        a, b, c = sets[i % R]
+        binding.check(fn(M, N, K, a, lda, b, ldb, c, ldc, sp))
     evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     evs[0].record(stream)
     for i in range(steps):
-        binding.check(fn(M, N, K, dA, lda, dB, ldb, dC, ldc, sp))
+        a, b, c = sets[(warmup + i) % R]
+        binding.check(fn(M, N, K, a, lda, b, ldb, c, ldc, sp))
         evs[i + 1].record(stream)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     per = [evs[i].elapsed_time(evs[i + 1]) for i in range(steps)]
     total = evs[0].elapsed_time(evs[steps])
     return total / steps, per, wall_ms / steps
+
+
+def rotation_sets(nbytes):
+    """Number of operand sets to rotate through so that a set has left the 256 MB
+    last-level cache before its turn comes again: at least 3, at least 1 GiB in
+    total, at most 64."""
+    return int(min(64, max(3, -(-(1 << 30) // max(nbytes, 1)))))
 
 
 def main():
@@ -96,6 +116,10 @@ def main():
                          "(calibration of the FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
     ap.add_argument("--sweep", action="store_true", help="also time every workload and the square sweep (extra lines on stderr)")
     ap.add_argument("--force-config", type=int, default=-1)
+    ap.add_argument("--rotate", default="auto", choices=["auto", "on", "off"],
+                    help="launch i works on operand set i mod R (R sets, 1 GiB or more in total), so that no launch finds "
+                         "its operands in the last-level cache; auto: for problems under 512 MiB, and the same-set "
+                         "figure is reported beside it")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -120,7 +144,7 @@ def main():
     binding.force_config(args.force_config)
     dev = torch.device("cuda:0")
 
-    def run_workload(name, mode, steps, warmup, shape=None):
+    def run_workload(name, mode, steps, warmup, shape=None, rotate=False):
         if shape is None:
             M, N, K, dab, dc, _ = wl.WORKLOADS[name]
         else:
@@ -128,17 +152,30 @@ def main():
         cdt = np.float32 if mode == "f32" else np.float16
         A, B, C0 = wl.make_inputs(M, N, K, dab, dc, seed=0, c_dtype=cdt)
         dA, dB, dC = (torch.from_numpy(x).to(dev) for x in (A, B, C0))
-        ms, per, wall = time_gemm(binding, torch, mode, M, N, K, dA, dB, dC, steps, warmup)
+        sets = [(dA, dB, dC)]
+        if rotate:
+            for _ in range(rotation_sets(algorithmic_bytes(M, N, K, 4 if mode == "f32" else 2)) - 1):
+                sets.append((dA.clone(), dB.clone(), dC.clone()))
+        ms, per, wall = time_gemm(binding, torch, mode, M, N, K, sets, steps, warmup)
         cfg = binding.query_config(mode == "f16", M, N, K, dA, dA.stride(0), dB, dB.stride(0), dC, dC.stride(0))
         flops = 2.0 * M * N * K
         if cfg.get("split_rows"):
             cfg["plan"] = f"{cfg['name']} on rows 0..{cfg['split_rows'] - 1} + {binding.describe_config(cfg['id2'])['name']} on the rest"
         else:
             cfg["plan"] = cfg["name"]
-        return dict(M=M, N=N, K=K, ms=ms, per=per, wall_ms=wall, tflops=flops / (ms * 1e-3) / 1e12, cfg=cfg,
+        return dict(M=M, N=N, K=K, ms=ms, per=per, wall_ms=wall, tflops=flops / (ms * 1e-3) / 1e12, cfg=cfg, sets=len(sets),
                     bytes=algorithmic_bytes(M, N, K, 4 if mode == "f32" else 2)), (A, B, C0)
 
-    r, (A, B, C0) = run_workload(args.workload, args.mode, args.steps, args.warmup)
+    # A problem whose operands fit the 256 MB last-level cache a few times over is
+    # timed on rotating operand sets (every launch reads from HBM); the figure with
+    # one set, re-read from the cache, is reported beside it.
+    def small(m, n, k, mode):
+        return algorithmic_bytes(m, n, k, 4 if mode == "f32" else 2) < ROTATE_BELOW_BYTES
+
+    m0, n0, k0 = wl.WORKLOADS[args.workload][:3]
+    rot = small(m0, n0, k0, args.mode) if args.rotate == "auto" else args.rotate == "on"
+    r, (A, B, C0) = run_workload(args.workload, args.mode, args.steps, args.warmup, rotate=rot)
+    same_set = run_workload(args.workload, args.mode, args.steps, args.warmup)[0] if rot and args.rotate == "auto" else None
     M, N, K = r["M"], r["N"], r["K"]
     per = sorted(r["per"])
     avg_launch_ms = sum(per) / len(per)
@@ -181,34 +218,44 @@ def main():
         "dtype": "f16 inputs, f32 accumulate" + ("" if args.mode == "f32" else ", f16 store"),
         "data": "synthetic", "pct_of_f16_mfma_peak": round(100 * r["tflops"] / PEAK_F16_MFMA_TFLOPS, 2),
         "config": {"workload": f"{args.workload}: M={M} N={N} K={K}, mode {args.mode}", "tile": r["cfg"]["plan"],
-                   "grid": r["cfg"]["grid"], "host_wall_ms_per_step": round(r["wall_ms"], 5)},
+                   "grid": r["cfg"]["grid"], "host_wall_ms_per_step": round(r["wall_ms"], 5),
+                   "operand_sets": r["sets"]},
         "roofline": roofline, "cpu_baseline": cpu,
     }
+
+    if same_set is not None:
+        out["same_operands_every_launch"] = {"value": round(same_set["tflops"], 2), "ms_per_step": round(same_set["ms"], 5)}
 
     if args.sweep:
         # every point gets the same treatment as the headline: about 25 ms of
         # untimed launches first (the first launches after a pause run at a lower
         # clock), then about 40 ms of timed ones
-        def warm_run(name, mode, shape=None):
+        def warm_run(name, mode, shape=None, rotate=False):
             probe, _ = run_workload(name, mode, 3, 2, shape)
             est = max(probe["ms"], 1e-3)
-            return run_workload(name, mode, int(min(400, max(10, 40.0 / est))), int(min(400, max(3, 25.0 / est))), shape)
+            return run_workload(name, mode, int(min(400, max(10, 40.0 / est))), int(min(400, max(3, 25.0 / est))), shape,
+                                rotate=rotate)[0]
 
         extra = []
+
+        def point(label, name, mode, m, n, k, shape=None):
+            rr = warm_run(name, mode, shape)
+            row = {"workload": label, "mode": mode, "M": m, "N": n, "K": k, "ms": round(rr["ms"], 5),
+                   "tflops": round(rr["tflops"], 1), "pct_peak": round(100 * rr["tflops"] / PEAK_F16_MFMA_TFLOPS, 1),
+                   "gbs": round(rr["bytes"] / (rr["ms"] * 1e-3) / 1e9, 1), "tile": rr["cfg"]["plan"]}
+            if small(m, n, k, mode):            # the same point with every launch reading from HBM
+                rc = warm_run(name, mode, shape, rotate=True)
+                row.update({"rotated_sets": rc["sets"], "rotated_ms": round(rc["ms"], 5), "rotated_tflops": round(rc["tflops"], 1),
+                            "rotated_gbs": round(rc["bytes"] / (rc["ms"] * 1e-3) / 1e9, 1)})
+            extra.append(row)
+            print(json.dumps(row), file=sys.stderr, flush=True)
+
         for name, (m, n, k, _, _, modes) in wl.WORKLOADS.items():
             for mode in modes:
-                rr, _ = warm_run(name, mode)
-                extra.append({"workload": name, "mode": mode, "M": m, "N": n, "K": k, "ms": round(rr["ms"], 5),
-                              "tflops": round(rr["tflops"], 1), "pct_peak": round(100 * rr["tflops"] / PEAK_F16_MFMA_TFLOPS, 1),
-                              "gbs": round(rr["bytes"] / (rr["ms"] * 1e-3) / 1e9, 1), "tile": rr["cfg"]["plan"]})
-                print(json.dumps(extra[-1]), file=sys.stderr, flush=True)
+                point(name, name, mode, m, n, k)
         for n in wl.SQUARE_SWEEP:
             for mode in ("f32", "f16"):
-                rr, _ = warm_run(None, mode, shape=(n, n, n))
-                extra.append({"workload": f"square{n}", "mode": mode, "M": n, "N": n, "K": n, "ms": round(rr["ms"], 5),
-                              "tflops": round(rr["tflops"], 1), "pct_peak": round(100 * rr["tflops"] / PEAK_F16_MFMA_TFLOPS, 1),
-                              "gbs": round(rr["bytes"] / (rr["ms"] * 1e-3) / 1e9, 1), "tile": rr["cfg"]["plan"]})
-                print(json.dumps(extra[-1]), file=sys.stderr, flush=True)
+                point(f"square{n}", None, mode, n, n, n, shape=(n, n, n))
         out["sweep"] = extra
 
     print(json.dumps(out), flush=True)

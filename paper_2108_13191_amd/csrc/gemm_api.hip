@@ -10,8 +10,11 @@ namespace {
 // Configuration table: entry 0 is the any-shape kernel, entry 1 the 256 x 256
 // four-wavefront kernel, entries 2 and 3 the 256 x 256 phase-alternating
 // eight-wavefront kernel on 32x32x16 and on 16x16x32 MFMAs, then the generic
-// double-buffered tiles, then the 192 x 256, 128 x 256 and 128 x 128 forms of entry 3.
-int num_configs() { return 4 + tiled_num_configs() + 3; }
+// double-buffered tiles, then the 192 x 256, 128 x 256 and 128 x 128 forms of entry 3,
+// then two more launch forms of entry 3 for problems with several tiles per compute
+// unit: chained (one workgroup per unit walks its tiles) and staggered (every other
+// unit starts with half a tile).
+int num_configs() { return 4 + tiled_num_configs() + 5; }
 
 const GemmConfigDesc kGeneric = {
     "generic64x64x32", 64, 64, 32, 4, 32, 32, 2 * 64 * (32 + 8) * 2,
@@ -20,7 +23,9 @@ const GemmConfigDesc kGeneric = {
 const GemmConfigDesc* config(int id)
 {
     const int nt = tiled_num_configs();
-    if (id >= 4 + nt) return id == 4 + nt ? pingpong16_config(192, 256) : id == 5 + nt ? pingpong16_config(128, 256) : pingpong16_config(128, 128);
+    if (id >= 4 + nt)
+        return id == 4 + nt ? pingpong16_config(192, 256) : id == 5 + nt ? pingpong16_config(128, 256)
+             : id == 6 + nt ? pingpong16_config(128, 128) : id == 7 + nt ? pingpong16_persistent_config() : pingpong16_staggered_config();
     return id == 0 ? &kGeneric : id == 1 ? w4_config() : id == 2 ? pingpong_config() : id == 3 ? pingpong16_config(256, 256) : tiled_config(id - 4);
 }
 
@@ -104,7 +109,21 @@ int best_single(int64_t M, int64_t N, int64_t K, double* cost_out)
 // configuration suits the left-over rows best behind them -- 5120^3 is one full
 // round of 256 x 256 tiles plus one round of 192 x 256 tiles instead of two
 // rounds of which the second is 56 % full.
-Plan select_plan(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb)
+constexpr int ID_PP256 = 3;
+int id_chained() { return 4 + tiled_num_configs() + 3; }
+int id_staggered() { return 4 + tiled_num_configs() + 4; }
+
+// The 256 x 256 tiling runs chained when a compute unit gets more than one tile
+// (measured 1-5 % faster, more the shorter the k loop; the k-tail form is not:
+// it needs a few registers more than there are).
+int chained_if_it_pays(int id, int64_t rows, int64_t N, int64_t K)
+{
+    if (id != ID_PP256 || K % 64 != 0) return id;
+    const GemmConfigDesc* c = config(id_chained());
+    return c->grid(rows, N) < config(ID_PP256)->grid(rows, N) ? id_chained() : id;
+}
+
+Plan select_plan_unchained(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb)
 {
     if (!aligned_for_tiled(N, K, A, lda, B, ldb)) return {0, M, -1};
     if (g_forced >= 0 && g_forced < num_configs()) return {g_forced, M, -1};
@@ -112,6 +131,15 @@ Plan select_plan(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, co
     Plan best = {best_single(M, N, K, &cost), M, -1};
     const int64_t tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
     if (tiles_n > 256 || tiles_m < 2 || cost < 0) return best;
+    // Short k loops, two or more full rounds of 256 x 256 tiles and a last round at
+    // most half full: the staggered form fills that round with half tiles (and
+    // spreads the C traffic, which dominates such problems, over time).  With long
+    // k loops the two halves of the chip would no longer share operand panels in L2.
+    {
+        const int64_t tiles = tiles_m * tiles_n, full = tiles / 256, left = tiles % 256;
+        const double staggered = ((double)full + 0.55) * 65536.0;
+        if (K <= 1024 && full >= 2 && left > 0 && left <= 128 && staggered < cost) { cost = staggered; best = {id_staggered(), M, -1}; }
+    }
     const double second_launch = 3000.0;                  // drain and refill between the two launches
     const int64_t total_rounds = (tiles_m * tiles_n + 255) / 256;
     for (int64_t r = total_rounds > 4 ? total_rounds - 3 : 1; r <= total_rounds; r++) {   // the cut is near the end
@@ -120,9 +148,18 @@ Plan select_plan(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, co
         double rest = 0;
         const int id2 = best_single(M - 256 * j, N, K, &rest);
         const double first = (double)((j * tiles_n + 255) / 256) * 65536.0;
-        if (rest >= 0 && first + rest + second_launch < cost) { cost = first + rest + second_launch; best = {3, 256 * j, id2}; }
+        if (rest >= 0 && first + rest + second_launch < cost) { cost = first + rest + second_launch; best = {ID_PP256, 256 * j, id2}; }
     }
     return best;
+}
+
+Plan select_plan(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb)
+{
+    Plan pl = select_plan_unchained(M, N, K, A, lda, B, ldb);
+    if (g_forced >= 0 && g_forced < num_configs()) return pl;        // a forced configuration runs as it is
+    pl.id = chained_if_it_pays(pl.id, pl.rows1, N, K);
+    if (pl.id2 >= 0) pl.id2 = chained_if_it_pays(pl.id2, M - pl.rows1, N, K);
+    return pl;
 }
 
 void fill_desc(int id, int64_t grid, gemm_f16_config* out, int64_t split_rows = 0, int id2 = -1)

@@ -90,9 +90,22 @@ template <int V> struct IntTag { static constexpr int value = V; };
 // fills the compute units better that way (the wavefront tile is then 96 x 64 /
 // 64 x 64; everything else is unchanged).  BN = its columns: 256, or 128 (wavefront
 // tile 32 columns wide) for the small-problem form 128 x 128.
-template <typename CT, int MI, bool TAIL, int BM, int BN>
-__global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
+template <int BM, int BN>
+constexpr int pp_lds_bytes() { return 2 * (BM * BK * 2) + 3 * (BK * BN * 2); }     // 160 KB for 256 x 256
+
+// One BM x BN tile of C with its first row and column at (m0, n0), by the whole
+// workgroup; smem_base = LDS address of pp_lds_bytes<BM, BN>() bytes, 1 KB aligned.
+// PERSIST: afterwards the tiles next_tile, next_tile + tile_step, ... (indices as
+// for tile_of_block) as long as they exist.  The copies of a tile's k step 0 are
+// then issued before the epilogue of the tile before it, those of k step 1 right
+// after it, so that a tile's first operands cross the memory system while C is
+// read and written; the epilogue's transposing buffers lie in the LDS that k step
+// 0 does not use.
+template <typename CT, int MI, bool TAIL, int BM, int BN, bool PERSIST = false>
+__device__ __forceinline__ void pp_tile(const TiledParams& p, const uint32_t smem_base, int m0, int n0,
+                                        int next_tile = 0, const int tile_step = 0)
 {
+    static_assert(!PERSIST || (BM == 256 && BN == 256), "the relocated epilogue buffers are laid out for 256 x 256");
     constexpr int HM = BM / 2;                       // rows per wavefront group
     constexpr int WN = BN / 4;                       // columns per wavefront
     constexpr int B_BUF = BK * BN * 2;               // 32 KB for BN = 256
@@ -100,21 +113,13 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     constexpr int TB = BN / 64;                      // copies per wavefront and B half
     constexpr int A_BUF = BM * BK * 2;               // 32 KB for BM = 256
     constexpr int B_REGION = 2 * A_BUF;
-    constexpr int PP_LDS = 2 * A_BUF + 3 * B_BUF;    // 160 KB for BM = 256
     constexpr int TA = HM / 32;                      // copies per wavefront and A half
-    __shared__ __attribute__((aligned(1024))) char smem[PP_LDS];
-    const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_ptr_t)smem;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int grp = wave >> 2;                 // 0: X (top rows), 1: Y (bottom rows)
     const int wn = wave & 3;                   // column block of 64; also the copy slot within the group
-
-    int tile_m, tile_n;
-    tile_of_block(p, blockIdx.x, tile_m, tile_n);
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
-    const bool edge = (m0 + BM > p.M) || (n0 + BN > p.N);
 
     const int kt_full = p.K / BK;
     const int KT = (p.K + BK - 1) / BK;
@@ -124,11 +129,14 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     // wavefronts of a group take copies q = wn + 4t.  Lane i writes (row
     // 8q + i/8, chunk position i%8), which must hold logical chunk
     // position ^ ((row/2)%8) -- a per-lane constant because q = wn (mod 2).
-    const half_t* const a_tile = p.A + (int64_t)m0 * p.lda;
-    const half_t* const b_tile = p.B + n0;
+    // (m0, n0, a_tile, b_tile and the lane offsets describe the tile being copied:
+    // under PERSIST they move on to the next tile before the epilogue)
+    const half_t* a_tile = p.A + (int64_t)m0 * p.lda;
+    const half_t* b_tile = p.B + n0;
     const int a_chunk = (lane & 7) ^ (4 * (wn & 1) + (lane >> 4));
-    auto a_offset = [&](int half, int t) -> uint32_t {
-        int row = half * HM + 8 * (wn + 4 * t) + (lane >> 3);
+    auto a_offset = [&](int half, int t, int ln) -> uint32_t {
+        const int a_chunk = (ln & 7) ^ (4 * (wn & 1) + (ln >> 4));
+        int row = half * HM + 8 * (wn + 4 * t) + (ln >> 3);
         row = (m0 + row < p.M) ? row : p.M - 1 - m0;                 // clamp: loaded, never stored
         return ((uint32_t)row * (uint32_t)p.lda + 8 * a_chunk) * 2;
     };
@@ -140,10 +148,10 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     // of the 16-lane blocks that read k and k+8 together (16x16x32 operands).
     constexpr int CPR = B_ROW / 16, RPC = 64 / CPR;                  // chunks per k row, k rows per copy
     auto b_krow = [&](int t) -> int { return RPC * (wn + 4 * t) + lane / CPR; };   // within the half
-    auto b_offset = [&](int t) -> uint32_t {                          // relative to the half's first k row
-        const int krow = b_krow(t);
+    auto b_offset = [&](int t, int ln) -> uint32_t {                  // relative to the half's first k row
+        const int krow = RPC * (wn + 4 * t) + ln / CPR;
         const int swz = ((krow & 3) << 2) | (((krow >> 3) & 1) << 1);
-        int col = 8 * ((lane % CPR) ^ swz);
+        int col = 8 * ((ln % CPR) ^ swz);
         if (n0 + col + 8 > p.N) col = 0;                              // clamp: loaded, never stored
         return ((uint32_t)krow * (uint32_t)p.ldb + col) * 2;
     };
@@ -181,11 +189,10 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     // in the A rows it reads itself and one k half of B for both groups.
     uint32_t a_off[4], b_off[4];
 #pragma unroll
-    for (int t = 0; t < 4; t++) { a_off[t] = t < TA ? a_offset(grp, t) : 0u; b_off[t] = t < TB ? b_offset(t) : 0u; }
+    for (int t = 0; t < 4; t++) { a_off[t] = t < TA ? a_offset(grp, t, lane) : 0u; b_off[t] = t < TB ? b_offset(t, lane) : 0u; }
 
     // ---- prologue: k steps 0 and 1 ---------------------------------------------
-#pragma unroll
-    for (int s = 0; s < 2; s++)
+    auto issue_k_step = [&](int s) {          // all of this wavefront's copies of k step s (0 or 1)
         if (s < KT) {
             if (!TAIL || s < kt_full) {
 #pragma unroll
@@ -195,7 +202,21 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
                 for (int t = 0; t < 4; t++) { if (t < TA) copy_a_part(s, grp, a_off, t, BoolTag<false>{}); if (t < TB) copy_b_part(s, grp, b_off, t, BoolTag<false>{}); }
             }
         }
+    };
+    issue_k_step(0);
+    issue_k_step(1);
 
+    bool chained = false;
+    for (;;) {      // one tile per trip (a single trip unless PERSIST)
+    const int cm0 = m0, cn0 = n0;             // the tile being multiplied and stored
+    // Per-lane addresses that are the same for every tile are derived again per tile
+    // from this copy of the lane number, which the compiler cannot see through:
+    // kept across the whole loop they would not fit the register file beside the
+    // accumulators and would be spilled, and reloading a spilled value waits for
+    // every load and store in flight.
+    int lane_t = lane;
+    if constexpr (PERSIST) asm volatile("" : "+v"(lane_t));
+    const bool edge = (cm0 + BM > p.M) || (cn0 + BN > p.N);
     // ---- accumulators -------------------------------------------------------
     // They start at zero; C is read once, in the epilogue, and added there
     // (C + sum formed as sum + C).  The MFMA is issued with the B fragment
@@ -213,8 +234,8 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
 #pragma unroll
             for (int i = 0; i < MI * MI / 64; i++) acc[fm][fn][i] = 0.0f;
     CT* const Cbase = (CT*)p.C;
-    const int crow0 = m0 + grp * HM;
-    const int ccol0 = n0 + wn * WN;
+    const int crow0 = cm0 + grp * HM;
+    const int ccol0 = cn0 + wn * WN;
 
     // ---- fragment read addresses ----------------------------------------------
     // MI = 32: A operand lane l holds tile row l%32 of its block, k = 8*(l/32)..+7 of
@@ -224,7 +245,7 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     constexpr int NSL = (MI == 32) ? 4 : 2;          // k slices per k step
     uint32_t a_rd[NSL];
     {
-        const int lr = lane & (MI - 1), lk = lane / MI;
+        const int lr = lane_t & (MI - 1), lk = lane_t / MI;
         const uint32_t row_off = (uint32_t)(grp * HM + lr) * (BK * 2);
         const int sw = (lr >> 1) & 7;
 #pragma unroll
@@ -238,7 +259,7 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     // MI = 16: block b covers k 8b..8b+7 of the 32-wide slice.
     uint32_t b_rd[FN];
     {
-        const int blk = lane >> 4, j = lane & 15;
+        const int blk = lane_t >> 4, j = lane_t & 15;
         const int krow = (MI == 32) ? 8 * (blk >> 1) + (j >> 2) : 8 * blk + (j >> 2);   // first read; +4 second
         const int swz = ((krow & 3) << 2) | (((krow >> 3) & 1) << 1);                    // unchanged by +4, +16, +32
 #pragma unroll
@@ -336,10 +357,18 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     // k step 0 has landed before phase 0; the 8 copies of k step 1 (issued
     // behind it, completing in order) may still be on their way -- the wait at
     // the end of k step 0 covers them
-    if (1 < kt_full) {
-        asm volatile("s_waitcnt vmcnt(%0)" :: "n"(TA + TB) : "memory");
-    } else {
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    // (A chained tile's k step 0 was requested before the epilogue of the tile
+    // before it and that epilogue has since consumed C loads requested later: loads
+    // complete in order, so it has landed.  Not waiting here matters: a wait would
+    // also count the C stores just issued.)
+    if (!PERSIST || !chained) {
+        if (1 < kt_full) {
+            asm volatile("s_waitcnt vmcnt(%0)" :: "n"(TA + TB) : "memory");
+        } else {
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        }
+    } else if (TAIL && kt_full < 1) {
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");       // k step 0 went through registers
     }
     phase_barrier();
 
@@ -359,11 +388,17 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     // leave exactly these loads outstanding).
     typedef typename CVec4<CT>::type ctx4;
     constexpr int PITCH = WN * 4 + 16;                       // 272 B for 64 columns
-    const uint32_t tbuf = smem_base + (uint32_t)wave * (32u * PITCH);
+    // (PERSIST: in the second A buffer and the second and third B buffers, which the
+    // next tile's k step 0 leaves alone)
+    const uint32_t tbuf = !PERSIST ? smem_base + (uint32_t)wave * (32u * PITCH)
+                        : wave < 3 ? smem_base + A_BUF + (uint32_t)wave * (32u * PITCH)
+                                   : smem_base + B_REGION + B_BUF + (uint32_t)(wave - 3) * (32u * PITCH);
     // where this lane's 4 consecutive columns of a block go: row l%MI, column 4*(l/MI) (+ block offsets)
-    const uint32_t w_addr = tbuf + (uint32_t)(lane & (MI - 1)) * PITCH + (uint32_t)(lane / MI) * 16;
-    const uint32_t r_addr = tbuf + (uint32_t)(lane / LPR) * PITCH + (uint32_t)(lane % LPR) * 16;
-    const int orow = lane / LPR, ocol = 4 * (lane % LPR);     // this lane's row (of RPP) and column in a pass
+    int lane_e = lane;
+    if constexpr (PERSIST) asm volatile("" : "+v"(lane_e));
+    const uint32_t w_addr = tbuf + (uint32_t)(lane_e & (MI - 1)) * PITCH + (uint32_t)(lane_e / MI) * 16;
+    const uint32_t r_addr = tbuf + (uint32_t)(lane_e / LPR) * PITCH + (uint32_t)(lane_e % LPR) * 16;
+    const int orow = lane_e / LPR, ocol = 4 * (lane_e % LPR);     // this lane's row (of RPP) and column in a pass
     const bool col_ok = !edge || (ccol0 + ocol < p.N);         // N is a multiple of 8: all 4 columns or none
     CT* const cptr = Cbase + (int64_t)(crow0 + orow) * p.ldc + ccol0 + ocol;
     float bias4[4] = {0.0f, 0.0f, 0.0f, 0.0f};              // fused epilogue: this lane's 4 columns of the bias
@@ -377,7 +412,7 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
         for (int ps = 0; ps < PASSES; ps++) {
             const bool ok = col_ok && (!edge || (crow0 + fm * 32 + RPP * ps + orow < p.M));
             // a group outside C reads this lane's first (valid or clamped) group of the tile instead
-            const CT* src = ok ? cptr + (int64_t)(fm * 32 + RPP * ps) * p.ldc : Cbase + (int64_t)m0 * p.ldc + n0;
+            const CT* src = ok ? cptr + (int64_t)(fm * 32 + RPP * ps) * p.ldc : Cbase + (int64_t)cm0 * p.ldc + cn0;
             dst[ps] = *reinterpret_cast<const ctx4*>(src);
         }
     };
@@ -385,6 +420,25 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
     for (int f = 0; f < NPRE; f++) fetch(f, cin[f]);
     __builtin_amdgcn_sched_barrier(0);
     for (; k < KT; k++) k_step(k, IntTag<0>{});
+
+    // ---- PERSIST: the next tile's k step 0 on its way before this tile's epilogue ----
+    bool has_next = false;
+    if constexpr (PERSIST) {
+        has_next = next_tile < p.tiles_m * p.tiles_n;
+        if (has_next) {
+            int tm, tn;
+            tile_of_block(p, next_tile, tm, tn);
+            next_tile += tile_step;
+            m0 = tm * BM; n0 = tn * BN;
+            a_tile = p.A + (int64_t)m0 * p.lda;
+            b_tile = p.B + n0;
+            int ln = lane;
+            asm volatile("" : "+v"(ln));
+#pragma unroll
+            for (int t = 0; t < 4; t++) { a_off[t] = t < TA ? a_offset(grp, t, ln) : 0u; b_off[t] = t < TB ? b_offset(t, ln) : 0u; }
+            issue_k_step(0);
+        }
+    }
 
     // ---- + C, -> C ---------------------------------------------------------------
     // Behind the last barrier nobody reads the A/B buffers any more, so each
@@ -424,6 +478,68 @@ __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
             }
         }
     }
+    if (!PERSIST || !has_next) break;
+    // every wavefront is done with its transposing buffer: k step 1 may overwrite them
+    phase_barrier();
+    {   // the lane offsets once more (not kept across the epilogue)
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+#pragma unroll
+        for (int t = 0; t < 4; t++) { a_off[t] = t < TA ? a_offset(grp, t, ln) : 0u; b_off[t] = t < TB ? b_offset(t, ln) : 0u; }
+    }
+    issue_k_step(1);
+    chained = true;
+    }   // tiles
+}
+
+template <typename CT, int MI, bool TAIL, int BM, int BN>
+__global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
+{
+    __shared__ __attribute__((aligned(1024))) char smem[pp_lds_bytes<BM, BN>()];
+    int tile_m, tile_n;
+    tile_of_block(p, blockIdx.x, tile_m, tile_n);
+    pp_tile<CT, MI, TAIL, BM, BN>(p, (uint32_t)(uintptr_t)(lds_ptr_t)smem, tile_m * BM, tile_n * BN);
+}
+
+// One workgroup per compute unit walks the tiles blockIdx.x, blockIdx.x + gridDim.x,
+// ... (the same tiles, in the same order, that the hardware would hand that unit
+// when every tile is a workgroup of its own and all tiles take equally long).
+template <typename CT, int MI, bool TAIL>
+__global__ __launch_bounds__(512) void gemm_pp256_persistent_kernel(const TiledParams p)
+{
+    __shared__ __attribute__((aligned(1024))) char smem[pp_lds_bytes<256, 256>()];
+    int tile_m, tile_n;
+    tile_of_block(p, blockIdx.x, tile_m, tile_n);
+    pp_tile<CT, MI, TAIL, 256, 256, true>(p, (uint32_t)(uintptr_t)(lds_ptr_t)smem, tile_m * 256, tile_n * 256,
+                                          (int)(blockIdx.x + gridDim.x), (int)gridDim.x);
+}
+
+// The 256 x 256 tiling with the first-generation workgroups of every other compute
+// unit (block index bit 5: the hardware hands consecutive workgroups to the 8 XCDs
+// in turn and, within an XCD, to its 4 shader engines in turn) taking only the top
+// 128 rows of their tile; the bottom halves come last in the grid.  Those units
+// then stay half a tile ahead of the others for the whole launch, so that at any
+// time about half the chip is in its epilogue -- the C read and write, which on
+// short-K problems saturates HBM when all units do it at once -- while the other
+// half multiplies.  Results do not depend on where workgroups actually land.
+constexpr int MIXED_HALVES = 128;
+template <typename CT, int MI, bool TAIL>
+__global__ __launch_bounds__(512) void gemm_pp_mixed_kernel(const TiledParams p)
+{
+    __shared__ __attribute__((aligned(1024))) char smem[pp_lds_bytes<256, 256>()];
+    const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_ptr_t)smem;
+    const int tiles = p.tiles_m * p.tiles_n;
+    int b = blockIdx.x, half = -1;
+    if (b >= tiles) { const int r = b - tiles; b = ((r >> 5) << 6) | 32 | (r & 31); half = 1; }   // r-th block of the first 256 with bit 5 set
+    else if (b < 256 && (b & 32)) half = 0;
+    int tile_m, tile_n;
+    tile_of_block(p, b, tile_m, tile_n);
+    if (half < 0) {
+        pp_tile<CT, MI, TAIL, 256, 256>(p, smem_base, tile_m * 256, tile_n * 256);
+    } else {
+        const int m0 = tile_m * 256 + 128 * half;
+        if (m0 < p.M) pp_tile<CT, MI, TAIL, 128, 256>(p, smem_base, m0, tile_n * 256);
+    }
 }
 
 template <int BM, int BN>
@@ -457,6 +573,77 @@ int launch_pp(const GemmArgs& a)
     return hipGetLastError() == hipSuccess ? GEMM_F16_OK : GEMM_F16_ERR_LAUNCH;
 }
 
+// fewer than two tiles per compute unit: nothing to stagger, the plain tiling runs
+int64_t grid_pp_mixed(int64_t M, int64_t N)
+{
+    const int64_t g = grid_pp<256, 256>(M, N);
+    return g < 512 ? g : g + MIXED_HALVES;
+}
+
+int launch_pp_mixed(const GemmArgs& a)
+{
+    const int64_t g = grid_pp_mixed(a.M, a.N);
+    if (g < 0 || g > INT32_MAX) return GEMM_F16_ERR_SIZE;
+    if (g < 512) return launch_pp<16, 256, 256>(a);
+    TiledParams p;
+    p.M = (int)a.M; p.N = (int)a.N; p.K = (int)a.K;
+    p.A = a.A; p.lda = a.lda; p.B = a.B; p.ldb = a.ldb; p.C = a.C; p.ldc = a.ldc;
+    p.bias = a.bias; p.relu = a.relu;
+    p.tiles_m = (int)((a.M + 255) / 256);
+    p.tiles_n = (int)((a.N + 255) / 256);
+    p.group_m = 8 < p.tiles_m ? 8 : p.tiles_m;
+    const bool tail = (a.K % BK) != 0;
+    if (a.c_is_f16) {
+        if (tail) hipLaunchKernelGGL((gemm_pp_mixed_kernel<half_t, 16, true>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
+        else      hipLaunchKernelGGL((gemm_pp_mixed_kernel<half_t, 16, false>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
+    } else {
+        if (tail) hipLaunchKernelGGL((gemm_pp_mixed_kernel<float, 16, true>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
+        else      hipLaunchKernelGGL((gemm_pp_mixed_kernel<float, 16, false>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
+    }
+    return hipGetLastError() == hipSuccess ? GEMM_F16_OK : GEMM_F16_ERR_LAUNCH;
+}
+
+int compute_units()
+{
+    static int n = 0;            // the same on every call; a data race here is benign
+    if (n == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+        n = v;
+    }
+    return n;
+}
+
+int64_t grid_pp_persistent(int64_t M, int64_t N)
+{
+    const int64_t g = grid_pp<256, 256>(M, N);
+    return g < compute_units() ? g : compute_units();
+}
+
+int launch_pp_persistent(const GemmArgs& a)
+{
+    const int64_t tiles = grid_pp<256, 256>(a.M, a.N);
+    if (tiles < 0) return GEMM_F16_ERR_SIZE;
+    if (tiles <= compute_units()) return launch_pp<16, 256, 256>(a);      // one tile each: nothing to chain
+    const unsigned g = (unsigned)compute_units();
+    TiledParams p;
+    p.M = (int)a.M; p.N = (int)a.N; p.K = (int)a.K;
+    p.A = a.A; p.lda = a.lda; p.B = a.B; p.ldb = a.ldb; p.C = a.C; p.ldc = a.ldc;
+    p.bias = a.bias; p.relu = a.relu;
+    p.tiles_m = (int)((a.M + 255) / 256);
+    p.tiles_n = (int)((a.N + 255) / 256);
+    p.group_m = 8 < p.tiles_m ? 8 : p.tiles_m;
+    const bool tail = (a.K % BK) != 0;
+    if (a.c_is_f16) {
+        if (tail) hipLaunchKernelGGL((gemm_pp256_persistent_kernel<half_t, 16, true>), dim3(g), dim3(512), 0, a.stream, p);
+        else      hipLaunchKernelGGL((gemm_pp256_persistent_kernel<half_t, 16, false>), dim3(g), dim3(512), 0, a.stream, p);
+    } else {
+        if (tail) hipLaunchKernelGGL((gemm_pp256_persistent_kernel<float, 16, true>), dim3(g), dim3(512), 0, a.stream, p);
+        else      hipLaunchKernelGGL((gemm_pp256_persistent_kernel<float, 16, false>), dim3(g), dim3(512), 0, a.stream, p);
+    }
+    return hipGetLastError() == hipSuccess ? GEMM_F16_OK : GEMM_F16_ERR_LAUNCH;
+}
+
 constexpr int lds_pp(int bm, int bn) { return 2 * bm * BK * 2 + 3 * BK * bn * 2; }
 const GemmConfigDesc kPingPong = {
     "pp256x256x64_w2x4", 256, 256, BK, 8, 128, 64, lds_pp(256, 256), true, launch_pp<32, 256, 256>, grid_pp<256, 256>};
@@ -468,9 +655,15 @@ const GemmConfigDesc kPingPong16_128 = {
     "pp128x256x64_w2x4_mi16", 128, 256, BK, 8, 64, 64, lds_pp(128, 256), true, launch_pp<16, 128, 256>, grid_pp<128, 256>};
 const GemmConfigDesc kPingPong16_128x128 = {
     "pp128x128x64_w2x4_mi16", 128, 128, BK, 8, 64, 32, lds_pp(128, 128), true, launch_pp<16, 128, 128>, grid_pp<128, 128>};
+const GemmConfigDesc kPingPong16Mixed = {
+    "pp256x256x64_w2x4_mi16_stag", 256, 256, BK, 8, 128, 64, lds_pp(256, 256), true, launch_pp_mixed, grid_pp_mixed};
+const GemmConfigDesc kPingPong16Persistent = {
+    "pp256x256x64_w2x4_mi16_chain", 256, 256, BK, 8, 128, 64, lds_pp(256, 256), true, launch_pp_persistent, grid_pp_persistent};
 
 }  // namespace
 
+const GemmConfigDesc* pingpong16_persistent_config() { return &kPingPong16Persistent; }
+const GemmConfigDesc* pingpong16_staggered_config() { return &kPingPong16Mixed; }
 const GemmConfigDesc* pingpong_config() { return &kPingPong; }
 const GemmConfigDesc* pingpong16_config(int bm, int bn)
 {

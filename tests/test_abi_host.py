@@ -69,7 +69,9 @@ def test_config_table_and_selection(lib):
     with pytest.raises(binding.GemmError):
         binding.describe_config(n)
     big = binding.query_config(0, 8192, 8192, 8192, 16, 8192, 16, 8192, 16, 8192)
-    assert big["block_m"] * big["block_n"] >= 128 * 128 and big["grid"] == (8192 // big["block_m"]) * (8192 // big["block_n"])
+    tiles = (8192 // big["block_m"]) * (8192 // big["block_n"])
+    # (the chained form of the large tile runs one workgroup per compute unit, 256 on an MI355X and without a GPU)
+    assert big["block_m"] * big["block_n"] >= 128 * 128 and big["grid"] == (256 if big["name"].endswith("_chain") else tiles)
     small = binding.query_config(0, 256, 256, 256, 16, 256, 16, 256, 16, 256)
     assert small["block_m"] <= 128     # small problems take small tiles (more workgroups)
     # anything unaligned goes to the any-shape kernel
@@ -105,7 +107,7 @@ int main(void) {
     if (gemm_f16_num_configs() < 1) return 1;
     if (gemm_f16_describe_config(0, &c) != GEMM_F16_OK || strlen(c.name) == 0) return 2;
     if (gemm_f16_query_config(0, 8192, 8192, 8192, (void*)256, 8192, (void*)256, 8192, (void*)256, 8192, &c) != GEMM_F16_OK) return 3;
-    if (c.block_m != 256 || c.grid != 1024) return 4;
+    if (c.block_m != 256 || (c.grid != 1024 && c.grid != 256)) return 4;
     if (gemm_f16_f32acc(-1, 1, 1, 0, 1, 0, 1, 0, 1, 0) != GEMM_F16_ERR_SIZE) return 5;
     if (gemm_f16_f32acc_bias_act(4, 4, 4, (void*)256, 4, (void*)256, 4, (float*)256, 4, 0, 9, 0) != GEMM_F16_ERR_CONFIG) return 6;
     printf("%s\\n", gemm_strerror(GEMM_F16_ERR_PITCH));
