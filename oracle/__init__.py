@@ -123,6 +123,24 @@ def bias_act(Cref: np.ndarray, bias=None, relu: bool = False) -> np.ndarray:
     return out
 
 
+def gemm_f16_rounding_every_slice(A: np.ndarray, B: np.ndarray, C0: np.ndarray, slice_k: int = 16) -> np.ndarray:
+    """A literal reading of the paper's half-precision mode (section Half Precision
+    Performance: the accumulation is done in binary16 too): the running sum is a
+    binary16 value, and each slice of `slice_k` products (16 = the depth of the
+    paper's m16n16k16 operation) is added to it exactly and the sum rounded to
+    nearest even.  NOT the parity reference -- the library accumulates the whole
+    k range in binary32 and rounds once, which `round_to_f16(gemm_f16(...)[0])`
+    describes; this function exists to put a number on the difference between
+    the two readings.  Returns binary64 values that are binary16-representable."""
+    A64, B64 = np.asarray(A, np.float16).astype(np.float64), np.asarray(B, np.float16).astype(np.float64)
+    acc = np.asarray(C0, np.float16).astype(np.float64)
+    K = A64.shape[1]
+    for k0 in range(0, K, slice_k):
+        # <= slice_k products of 22-bit significands: the binary64 sum is exact to far below half a binary16 ulp
+        acc = round_to_f16(acc + A64[:, k0:k0 + slice_k] @ B64[k0:k0 + slice_k, :]).astype(np.float64)
+    return acc
+
+
 def f16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
     """Decode binary16 bit patterns (uint16) to float64 with the oracle's decoder."""
     bits = np.ascontiguousarray(bits, dtype=np.uint16)

@@ -326,3 +326,41 @@ def test_bias_act_composes_with_gemm(oracle_mod):
     Cref, _ = oracle_mod.gemm_f16(A, B, C0)
     want = np.maximum(A.astype(np.float64) @ B.astype(np.float64) + C0 + bias[None, :], 0.0)
     assert np.array_equal(oracle_mod.bias_act(Cref, bias, True), want)
+
+
+# ---- the literal binary16-accumulating reading (a numerical comparison, not the parity reference) ----
+
+def test_rounding_every_slice_closed_forms(oracle_mod):
+    rng = np.random.default_rng(21)
+    A = rng.integers(-2, 3, (24, 96)).astype(np.float16)
+    B = rng.integers(-2, 3, (96, 40)).astype(np.float16)
+    C0 = rng.integers(-4, 5, (24, 40)).astype(np.float16)
+    # small integers: every partial sum is a binary16 value, so no rounding happens at any slice width
+    exact = A.astype(np.int64) @ B.astype(np.int64) + C0.astype(np.int64)
+    for w in (1, 16, 32, 96):
+        assert np.array_equal(oracle_mod.gemm_f16_rounding_every_slice(A, B, C0, w), exact.astype(np.float64))
+    # one slice over the whole k range = one rounding of the exact result
+    A = rng.uniform(-1, 1, (16, 80)).astype(np.float16)
+    B = rng.uniform(-1, 1, (80, 24)).astype(np.float16)
+    C0 = rng.uniform(-1, 1, (16, 24)).astype(np.float16)
+    Cref, _ = oracle_mod.gemm_f16(A, B, C0)
+    assert np.array_equal(oracle_mod.gemm_f16_rounding_every_slice(A, B, C0, 80), oracle_mod.round_to_f16(Cref).astype(np.float64))
+    # 2049 ones: 2048 + 1 is a tie in binary16 and goes to even (2048) when every product is rounded in
+    ones = np.ones((1, 2049), np.float16)
+    assert oracle_mod.gemm_f16_rounding_every_slice(ones, ones.T.copy(), np.zeros((1, 1), np.float16), 1)[0, 0] == 2048.0
+    assert oracle_mod.round_to_f16(oracle_mod.gemm_f16(ones, ones.T.copy(), np.zeros((1, 1), np.float16))[0])[0, 0] == 2048.0  # 2049 -> tie -> 2048
+    ones = np.ones((1, 2051), np.float16)           # 2051 rounds to 2052 in one rounding; one at a time it never leaves 2048
+    assert oracle_mod.round_to_f16(oracle_mod.gemm_f16(ones, ones.T.copy(), np.zeros((1, 1), np.float16))[0])[0, 0] == 2052.0
+    assert oracle_mod.gemm_f16_rounding_every_slice(ones, ones.T.copy(), np.zeros((1, 1), np.float16), 1)[0, 0] == 2048.0
+
+
+def test_round_on_store_is_the_more_accurate_reading(oracle_mod):
+    """Both readings of the half-precision mode stay inside 4e-3 * sum|a||b| on the
+    headline's data; rounding at every 16-deep slice loses about ten times more."""
+    K = 4096
+    A, B, C0 = wl.make_inputs(40, 48, K, "normal_rsqrtk", "zeros", seed=2, c_dtype=np.float16)
+    Cref, S = oracle_mod.gemm_f16(A, B, C0)
+    once = np.abs(oracle_mod.round_to_f16(Cref).astype(np.float64) - Cref) / S
+    sliced = np.abs(oracle_mod.gemm_f16_rounding_every_slice(A, B, C0, 16) - Cref) / S
+    assert once.max() <= 2.0 ** -11 and sliced.max() <= 4e-3
+    assert sliced.max() > 3 * once.max() and sliced.mean() > 3 * once.mean()
