@@ -49,7 +49,10 @@ def kernel_symbol(tile_name, mode, K=0):
         return f"gemm_w4_kernel<{ct}>"
     if tile_name.startswith("generic"):
         return f"gemm_generic_kernel<{ct}>"
-    return f"gemm_tiled_kernel<{tile_name}, {ct}>"
+    # t<BM>x<BN>x64_w<WM>x<WN>: template arguments BM, BN, waves along m, along n, LDS stages, C type
+    import re
+    bm, bn, wm, wn = (int(x) for x in re.match(r"t(\d+)x(\d+)x\d+_w(\d+)x(\d+)", tile_name).groups())
+    return f"gemm_tiled_kernel<{bm}, {bn}, {wm}, {wn}, {4 if bm == 64 else 2}, {ct}>"
 
 
 def measured_traffic(tile_name, workload, mode):

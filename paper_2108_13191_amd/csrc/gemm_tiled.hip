@@ -33,9 +33,15 @@ namespace {
 
 using namespace gemm_dev;
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, typename CT>
+// STAGES = LDS buffers (a power of two): the copies of k step kt + STAGES are
+// issued in k step kt, so that many k steps of A and B are on their way at any
+// time.  Two are enough when a k step's MFMAs outlast the memory latency (large
+// tiles); a 64 x 64 tile multiplies a k step in about 60 ns and would otherwise
+// spend its time waiting for every k step in turn.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, typename CT>
 __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_tiled_kernel(const TiledParams p)
 {
+    static_assert(STAGES >= 2 && (STAGES & (STAGES - 1)) == 0, "stage index is kt & (STAGES - 1)");
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int FM = WM / 32, FN = WN / 32;
@@ -52,7 +58,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_tiled_kernel(cons
     static_assert(A_INSTR % NW == 0 && B_INSTR % NW == 0, "copies must divide among the waves");
     static_assert(WM % 32 == 0 && WN % 32 == 0 && BN >= 64 && BN <= 512, "tile shape");
 
-    __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE];
+    __shared__ __attribute__((aligned(1024))) char smem[STAGES * STAGE];
     const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_ptr_t)smem;
 
     const int tid = threadIdx.x;
@@ -131,13 +137,13 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_tiled_kernel(cons
         }
     };
 
-    // ---- prologue: the first two k steps' copies, then the C tile ------------
+    // ---- prologue: the first STAGES k steps' copies, then the C tile ----------
 #pragma unroll
-    for (int i = 0; i < NC; i++) issue_copy(0, 0, i);
-    if (KT > 1) {
+    for (int s = 0; s < STAGES; s++)
+        if (s < KT) {
 #pragma unroll
-        for (int i = 0; i < NC; i++) issue_copy(1, 1, i);
-    }
+            for (int i = 0; i < NC; i++) issue_copy(s, s, i);
+        }
 
     // accumulator register i of lane l: row 8*(i/4) + 4*(l/32) + i%4, column l%32
     floatx16 acc[FM][FN];
@@ -200,14 +206,16 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_tiled_kernel(cons
 
     // ---- main loop -------------------------------------------------------------
     // One barrier per k step, placed in front of the last slice: behind it the
-    // stage just consumed is free (copies for k step kt+2 go there, a whole k
-    // step before they are needed) and the next stage is complete (its slice 0
-    // is fetched while the last slice is multiplied).  Every slice is cut into
+    // stage just consumed is free (copies for k step kt+STAGES go there) and the
+    // next stage is complete (its slice 0 is fetched while the last slice is
+    // multiplied).  Copies complete in order: with those of k steps kt+2 ..
+    // kt+STAGES-1 allowed to be outstanding, k step kt+1 has landed; in the last
+    // STAGES-1 k steps fewer are outstanding than that, so everything is awaited.  Every slice is cut into
     // FM chunks {a share of the next slice's LDS reads, a share of the copies,
     // one row of MFMAs}; the scheduler may reorder inside a chunk only, so LDS
     // and copy instructions are issued in the shadow of the MFMAs around them.
     for (int kt = 0; kt < KT; kt++) {
-        const uint32_t cur = (uint32_t)(kt & 1) * STAGE, nxt = cur ^ STAGE;
+        const uint32_t cur = (uint32_t)(kt & (STAGES - 1)) * STAGE, nxt = (uint32_t)((kt + 1) & (STAGES - 1)) * STAGE;
 #pragma unroll
         for (int ks = 0; ks < BK / 16 - 1; ks++) {
 #pragma unroll
@@ -222,11 +230,15 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_tiled_kernel(cons
         }
         // this wave's copies of k step kt+1 have landed and its reads of this
         // stage are complete; after the barrier that holds for every wave
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        if (STAGES > 2 && kt + STAGES <= kt_full) {      // (a k tail goes through registers, not through the counter's order)
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" :: "n"((STAGES - 2) * NC) : "memory");
+        } else {
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        }
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
-        const bool more = kt + 1 < KT, copy = kt + 2 < KT;
+        const bool more = kt + 1 < KT, copy = kt + STAGES < KT;
 #pragma unroll
         for (int c = 0; c < FM; c++) {
             if (more) {
@@ -235,7 +247,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_tiled_kernel(cons
             }
             if (copy) {
 #pragma unroll
-                for (int i = c * NC / FM; i < (c + 1) * NC / FM; i++) issue_copy(kt + 2, kt & 1, i);
+                for (int i = c * NC / FM; i < (c + 1) * NC / FM; i++) issue_copy(kt + STAGES, kt & (STAGES - 1), i);
             }
 #pragma unroll
             for (int fn = 0; fn < FN; fn++)
@@ -265,7 +277,7 @@ int64_t grid_tiled(int64_t M, int64_t N)
     return tm * tn;
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
 int launch_tiled(const GemmArgs& a)
 {
     const int64_t g = grid_tiled<BM, BN, WAVES_M, WAVES_N>(a.M, a.N);
@@ -281,20 +293,23 @@ int launch_tiled(const GemmArgs& a)
     if (p.group_m > p.tiles_m) p.group_m = p.tiles_m;
     constexpr int threads = WAVES_M * WAVES_N * 64;
     if (a.c_is_f16)
-        hipLaunchKernelGGL((gemm_tiled_kernel<BM, BN, WAVES_M, WAVES_N, half_t>), dim3((unsigned)g), dim3(threads), 0, a.stream, p);
+        hipLaunchKernelGGL((gemm_tiled_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, half_t>), dim3((unsigned)g), dim3(threads), 0, a.stream, p);
     else
-        hipLaunchKernelGGL((gemm_tiled_kernel<BM, BN, WAVES_M, WAVES_N, float>), dim3((unsigned)g), dim3(threads), 0, a.stream, p);
+        hipLaunchKernelGGL((gemm_tiled_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, float>), dim3((unsigned)g), dim3(threads), 0, a.stream, p);
     return hipGetLastError() == hipSuccess ? GEMM_F16_OK : GEMM_F16_ERR_LAUNCH;
 }
 
-#define TILED_CONFIG(NAME, BM, BN, WMS, WNS)                                                     \
-    { NAME, BM, BN, BK, (WMS) * (WNS), (BM) / (WMS), (BN) / (WNS), 2 * ((BM) + (BN)) * BK * 2,   \
-      true, launch_tiled<BM, BN, WMS, WNS>, grid_tiled<BM, BN, WMS, WNS> }
+#ifndef T64_STAGES
+#define T64_STAGES 4
+#endif
+#define TILED_CONFIG(NAME, BM, BN, WMS, WNS, ST)                                                    \
+    { NAME, BM, BN, BK, (WMS) * (WNS), (BM) / (WMS), (BN) / (WNS), (ST) * ((BM) + (BN)) * BK * 2,   \
+      true, launch_tiled<BM, BN, WMS, WNS, ST>, grid_tiled<BM, BN, WMS, WNS> }
 
 const GemmConfigDesc kTiled[] = {
-    TILED_CONFIG("t256x256x64_w2x4", 256, 256, 2, 4),
-    TILED_CONFIG("t128x128x64_w2x2", 128, 128, 2, 2),
-    TILED_CONFIG("t64x64x64_w2x2", 64, 64, 2, 2),
+    TILED_CONFIG("t256x256x64_w2x4", 256, 256, 2, 4, 2),
+    TILED_CONFIG("t128x128x64_w2x2", 128, 128, 2, 2, 2),
+    TILED_CONFIG("t64x64x64_w2x2", 64, 64, 2, 2, T64_STAGES),
 };
 
 }  // namespace
