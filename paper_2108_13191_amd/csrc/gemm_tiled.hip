@@ -10,8 +10,8 @@
 //     kept in registers for the whole k loop (FM x FN accumulators of 32x32);
 //   * per k step of BK = 64 the A tile (BM x 64) and B tile (64 x BN) are
 //     copied global -> LDS by global_load_lds_dwordx4 (16 bytes per lane,
-//     written lane-linearly, no register staging), into one of two LDS
-//     buffers; one barrier per k step;
+//     written lane-linearly, no register staging), into one of a ring of LDS
+//     buffers (two; four for the 64 x 64 tile); one barrier per k step;
 //   * bank conflicts are avoided not by padding (the direct-to-LDS write is
 //     lane-linear) but by choosing which 16-byte chunk each lane fetches, so
 //     that the tile lands XOR-swizzled: A rows XOR their chunk index with
