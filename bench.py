@@ -45,6 +45,8 @@ def kernel_symbol(tile_name, mode, K=0):
         if tile_name.endswith("_stag"):
             return f"gemm_pp_mixed_kernel<{ct}, {mi}, {tail}>"
         return f"gemm_pp256_kernel<{ct}, {mi}, {'true' if K % 64 else 'false'}, {bm}, {bn}>"
+    if tile_name.startswith("ov"):
+        return f"gemm_pp_overlap_kernel<{ct}>"
     if tile_name.startswith("w4_"):
         return f"gemm_w4_kernel<{ct}>"
     if tile_name.startswith("generic"):

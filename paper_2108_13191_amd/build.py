@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgemm_f16.so")
-SOURCES = ["gemm_api.hip", "gemm_generic.hip", "gemm_tiled.hip", "gemm_pingpong.hip", "gemm_w4.hip"]
+SOURCES = ["gemm_api.hip", "gemm_generic.hip", "gemm_tiled.hip", "gemm_pingpong.hip", "gemm_overlap.hip", "gemm_w4.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
          # packed-f32 VALU forms are kept off for every HIP file of this library
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -14,7 +14,7 @@ namespace {
 // then two more launch forms of entry 3 for problems with several tiles per compute
 // unit: chained (one workgroup per unit walks its tiles) and staggered (every other
 // unit starts with half a tile).
-int num_configs() { return 4 + tiled_num_configs() + 5; }
+int num_configs() { return 4 + tiled_num_configs() + 6; }
 
 const GemmConfigDesc kGeneric = {
     "generic64x64x32", 64, 64, 32, 4, 32, 32, 2 * 64 * (32 + 8) * 2,
@@ -25,11 +25,30 @@ const GemmConfigDesc* config(int id)
     const int nt = tiled_num_configs();
     if (id >= 4 + nt)
         return id == 4 + nt ? pingpong16_config(192, 256) : id == 5 + nt ? pingpong16_config(128, 256)
-             : id == 6 + nt ? pingpong16_config(128, 128) : id == 7 + nt ? pingpong16_persistent_config() : pingpong16_staggered_config();
+             : id == 6 + nt ? pingpong16_config(128, 128) : id == 7 + nt ? pingpong16_persistent_config()
+             : id == 8 + nt ? pingpong16_staggered_config() : overlap_config();
     return id == 0 ? &kGeneric : id == 1 ? w4_config() : id == 2 ? pingpong_config() : id == 3 ? pingpong16_config(256, 256) : tiled_config(id - 4);
 }
 
 int g_forced = -1;
+
+}  // namespace
+
+// Compute units of the current device; the persistent kernels launch one workgroup
+// per unit.  The same on every call; a data race on the cached value is benign.
+int compute_units()
+{
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+        n = v;
+    }
+    return n;
+}
+
+namespace {
+
 
 int check_args(int c_is_f16, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
                const void* B, int64_t ldb, const void* C, int64_t ldc)

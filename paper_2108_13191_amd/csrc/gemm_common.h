@@ -50,5 +50,11 @@ const GemmConfigDesc* pingpong16_config(int block_m, int block_n);   // 256x256,
 const GemmConfigDesc* pingpong16_persistent_config();                 // 256x256, one workgroup per compute unit walks its tiles
 const GemmConfigDesc* pingpong16_staggered_config();                  // 256x256, every other compute unit half a tile ahead
 
+// gemm_overlap.hip
+const GemmConfigDesc* overlap_config();                              // 256x128, two accumulator sets: C traffic under the next tile's MFMAs
+
+// gemm_api.hip
+int compute_units();                                                 // of the current device (256 if there is none)
+
 // gemm_w4.hip
 const GemmConfigDesc* w4_config();

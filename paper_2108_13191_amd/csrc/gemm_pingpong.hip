@@ -603,17 +603,6 @@ int launch_pp_mixed(const GemmArgs& a)
     return hipGetLastError() == hipSuccess ? GEMM_F16_OK : GEMM_F16_ERR_LAUNCH;
 }
 
-int compute_units()
-{
-    static int n = 0;            // the same on every call; a data race here is benign
-    if (n == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
-        n = v;
-    }
-    return n;
-}
-
 int64_t grid_pp_persistent(int64_t M, int64_t N)
 {
     const int64_t g = grid_pp<256, 256>(M, N);

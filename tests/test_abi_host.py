@@ -120,3 +120,19 @@ int main(void) {
                     "-L", libdir, "-lgemm_f16", f"-Wl,-rpath,{libdir}"], check=True)
     out = subprocess.run([str(exe)], check=True, capture_output=True, text=True)
     assert "leading dimension" in out.stdout
+
+
+def test_overlap_kernel_keeps_in_flight_registers_untouched():
+    """gemm_overlap.hip uses loaded registers two k steps after the load without a wait the
+    compiler knows of; the generated code must not touch them in between."""
+    import shutil
+    if shutil.which("hipcc") is None:
+        pytest.skip("no hipcc")
+    from paper_2108_13191_amd import check_overlap_asm
+    # the scanner itself: a planted use of an in-flight register is found, a use after the marker is not
+    planted = ("_Zk:\n\tglobal_load_dwordx4 v[10:13], v[2:3], off ; C slab load\n\tv_add_f32_e32 v1, v11, v1\n"
+               "\t; C slab arrived v[10:13]\n\tv_add_f32_e32 v1, v12, v1\n")
+    loads, bad = check_overlap_asm.hazards(planted)
+    assert loads == 1 and [b[0] for b in bad] == [3]
+    loads, bad = check_overlap_asm.hazards(check_overlap_asm.compile_to_asm())
+    assert loads >= 64 and not bad, bad[:3]
