@@ -13,7 +13,8 @@ namespace {
 // double-buffered tiles, then the 192 x 256, 128 x 256 and 128 x 128 forms of entry 3,
 // then two more launch forms of entry 3 for problems with several tiles per compute
 // unit: chained (one workgroup per unit walks its tiles) and staggered (every other
-// unit starts with half a tile).
+// unit starts with half a tile); last the 256 x 128 kernel with two accumulator sets
+// (kept for comparison, never selected).
 int num_configs() { return 4 + tiled_num_configs() + 6; }
 
 const GemmConfigDesc kGeneric = {
