@@ -156,7 +156,10 @@ int gemm_f16_describe_config(int id, gemm_f16_config* out);
 /*
  * Benchmarking aid: force configuration `id` for every later call of this
  * process (id < 0 restores automatic selection).  A forced configuration whose
- * alignment requirements the call does not meet is ignored for that call.
+ * alignment requirements the call does not meet is ignored for that call;
+ * the launch forms made for several tiles per compute unit (names ending in
+ * _chain, _stag, and the ov... kernel) run the plain 256 x 256 tiling on
+ * problems they are not made for (few tiles, k tails, very short k loops).
  * Not thread-safe against concurrent GEMM calls.
  */
 int gemm_f16_force_config(int id);
