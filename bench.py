@@ -248,9 +248,13 @@ def main():
             row = {"workload": label, "mode": mode, "M": m, "N": n, "K": k, "ms": round(rr["ms"], 5),
                    "tflops": round(rr["tflops"], 1), "pct_peak": round(100 * rr["tflops"] / PEAK_F16_MFMA_TFLOPS, 1),
                    "gbs": round(rr["bytes"] / (rr["ms"] * 1e-3) / 1e9, 1), "tile": rr["cfg"]["plan"]}
+            # fraction of the roofline time max(flops / MFMA peak, algorithmic bytes / HBM peak)
+            t_roof = max(2.0 * m * n * k / (PEAK_F16_MFMA_TFLOPS * 1e12), rr["bytes"] / (PEAK_HBM_GBS * 1e9))
+            row["roofline_frac"] = round(t_roof / (rr["ms"] * 1e-3), 4)
             if small(m, n, k, mode):            # the same point with every launch reading from HBM
                 rc = warm_run(name, mode, shape, rotate=True)
                 row.update({"rotated_sets": rc["sets"], "rotated_ms": round(rc["ms"], 5), "rotated_tflops": round(rc["tflops"], 1),
+                            "rotated_roofline_frac": round(t_roof / (rc["ms"] * 1e-3), 4),
                             "rotated_gbs": round(rc["bytes"] / (rc["ms"] * 1e-3) / 1e9, 1)})
             extra.append(row)
             print(json.dumps(row), file=sys.stderr, flush=True)

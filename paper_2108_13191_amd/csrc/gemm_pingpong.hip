@@ -50,6 +50,13 @@
 // f16 C) of each wavefront's part of C are requested before the last two k
 // steps, which issue no copies, so that they arrive under those MFMAs.
 //
+// Launch forms (same tile body, pp_tile): one workgroup per tile (the hardware
+// hands tiles to compute units as they free up); chained -- one workgroup per
+// compute unit walks its tiles and requests a tile's first k step before the
+// epilogue of the tile before it; staggered -- every other compute unit starts
+// on half a tile (the 128-row form), so that the two halves of the chip read and
+// write C at different times.
+//
 // Requirements as for the other tuned kernels: A, B 16-byte aligned; lda, ldb,
 // K, N multiples of 8.  Rows >= M / columns >= N are fetched from clamped
 // addresses and never stored; the k tail is zero-filled through registers.

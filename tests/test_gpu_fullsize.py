@@ -1,11 +1,12 @@
 """GPU parity at the benchmark's full sizes, in the launch configuration that
 bench.py times (automatic kernel selection, dense leading dimensions).
 
-A full binary64 oracle pass over 8192^3 and above does not finish in seconds,
-so the oracle is evaluated on sampled rows of C (first, last, both sides of
-tile boundaries, random) x all N columns and compared element by element; a
-property test then covers EVERY output element of the 8192^3 launch with
-integer inputs whose exact result has a closed form.
+A full binary64 oracle pass over 8192^3 takes about half a minute on the box's
+host and is done once, for the headline launch (f32-accumulate); otherwise the
+oracle is evaluated on sampled rows of C (first, last, both sides of tile
+boundaries, random) x all N columns and compared element by element, and a
+property test covers EVERY output element of an 8192^3 launch with integer
+inputs whose exact result has a closed form.
 """
 import numpy as np
 import pytest
@@ -54,6 +55,26 @@ def test_headline_8192_sampled_rows(oracle_mod, mode):
     dC, cfg = _launch(A, B, C0, mode)
     r = _check_rows(oracle_mod, A, B, C0, dC, mode, 64, cfg["block_m"], f"8192^3 {mode}")
     print(f"8192^3 {mode}: tile {cfg['name']}, worst err/bound on {64} sampled rows {r:.3f}")
+
+
+def test_headline_8192_every_element(oracle_mod):
+    """The headline launch (f32-accumulate, bench.py's configuration) against a complete oracle
+    pass: all 8192 x 8192 outputs, in row blocks so that the binary64 reference and bound of a
+    block (2 x 64 MB) are all that is held at a time.  About half a minute of host time."""
+    A, B, C0 = wl.workload_inputs("sq8192_normal", "f32")
+    dC, cfg = _launch(A, B, C0, "f32")
+    got = dC.cpu().numpy()
+    M = A.shape[0]
+    worst = 0.0
+    for r0 in range(0, M, 1024):
+        rows = np.arange(r0, min(M, r0 + 1024), dtype=np.int64)
+        Cref, S = oracle_mod.gemm_f16(A, B, C0, rows=rows)
+        err = np.abs(got[rows].astype(np.float64) - Cref)
+        bound = TOL["f32"] * S
+        bad = ~(err <= bound)
+        assert not bad.any(), f"rows {r0}..: {bad.sum()} elements out of tolerance"
+        worst = max(worst, float(np.max(err / np.maximum(bound, 1e-300))))
+    print(f"8192^3 f32, every element: tile {cfg['name']}, worst err/bound {worst:.3f}")
 
 
 @pytest.mark.parametrize("name", ["ffn_up", "ffn_down", "qkv", "ragged4000"])
