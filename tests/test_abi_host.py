@@ -5,6 +5,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 from paper_2108_13191_amd import binding
@@ -136,3 +137,30 @@ def test_overlap_kernel_keeps_in_flight_registers_untouched():
     assert loads == 1 and [b[0] for b in bad] == [3]
     loads, bad = check_overlap_asm.hazards(check_overlap_asm.compile_to_asm())
     assert loads >= 64 and not bad, bad[:3]
+
+
+def test_plan_invariants_on_random_shapes(lib):
+    """Whatever the selector picks, the plan is well formed: the rows are covered once, a cut
+    lies on a 256-row boundary, every launch has workgroups, and the launch forms with
+    conditions are only chosen where they apply."""
+    rng = np.random.default_rng(12345)
+    n = binding.num_configs()
+    names = [binding.describe_config(i)["name"] for i in range(n)]
+    for _ in range(3000):
+        M = int(rng.integers(1, 20000))
+        N = int(rng.integers(1, 2500)) * 8
+        K = int(rng.integers(1, 1200)) * 8
+        q = binding.query_config(int(rng.integers(0, 2)), M, N, K, 256, K, 256, N, 256, N)
+        assert 0 < q["id"] < n and q["name"] == names[q["id"]] and q["grid"] >= 1, (M, N, K, q)
+        if q["split_rows"]:
+            assert 0 < q["split_rows"] < M and q["split_rows"] % 256 == 0 and 0 < q["id2"] < n, (M, N, K, q)
+            assert q["block_m"] == 256 and q["block_n"] == 256
+        else:
+            assert q["id2"] == -1
+        tiles256 = ((M + 255) // 256) * ((N + 255) // 256)
+        if q["name"].endswith("_chain"):
+            rows = q["split_rows"] or M
+            assert K % 64 == 0 and ((rows + 255) // 256) * ((N + 255) // 256) > 256 and (q["split_rows"] or q["grid"] == 256)
+        if q["name"].endswith("_stag"):
+            assert K <= 1024 and tiles256 >= 512 and 0 < tiles256 % 256 <= 128 and q["grid"] == tiles256 + 128
+        assert not q["name"].startswith("ov") and not q["name"].startswith("w4")      # comparison kernels are never selected

@@ -115,3 +115,28 @@ def test_every_element_of_8192_rank_one_b(oracle_mod):
     rows = wl.sample_rows(n, 8, cfg["block_m"], seed=5)
     Cref, _ = oracle_mod.gemm_f16(A, B, C0, rows=rows)
     assert np.array_equal(Cref, want[rows].astype(np.float64))
+
+
+def test_auto_selection_on_random_mid_size_shapes(oracle_mod):
+    """Seeded random problems large enough for every kind of plan (single launch of each tile
+    form, chained, staggered, row split), under automatic selection as bench.py runs it: sampled
+    rows against the oracle, both C types."""
+    rng = np.random.default_rng(2024)
+    seen = set()
+    shapes = [(int(rng.integers(2, 80)) * 128 - int(rng.integers(0, 2)) * int(rng.integers(1, 100)),
+               int(rng.integers(16, 900)) * 8,
+               int(rng.integers(8, 160)) * 8) for _ in range(14)]
+    shapes += [(16384, 2304, 512), (9216, 9216, 256), (7168, 7168, 192), (5120, 5120, 320)]   # staggered / split plans for certain
+    for idx, (M, N, K) in enumerate(shapes):
+        mode = "f32" if idx % 2 == 0 else "f16"
+        A, B, C0 = wl.make_inputs(M, N, K, "uniform", "uniform", seed=500 + idx, c_dtype=CDT[mode])
+        dC, cfg = _launch(A, B, C0, mode)
+        seen.add(cfg["name"] + ("+split" if cfg["split_rows"] else ""))
+        rows = wl.sample_rows(M, min(M, 48), cfg["block_m"], seed=idx)
+        Cref, S = oracle_mod.gemm_f16(A, B, C0, rows=rows)
+        got = dC[torch.from_numpy(rows).to(dC.device)].cpu().numpy().astype(np.float64)
+        bound = TOL[mode] * (S + np.abs(C0[rows].astype(np.float64)))
+        bad = ~(np.abs(got - Cref) <= bound)
+        assert not bad.any(), f"{(M, N, K)} {mode} {cfg['name']}: {bad.sum()} sampled elements out of tolerance"
+    print("plans exercised:", sorted(seen))
+    assert any(s.endswith("_chain") or "_chain+" in s for s in seen) and any("_stag" in s for s in seen) and any("+split" in s for s in seen)
