@@ -110,8 +110,9 @@ def rotation_sets(nbytes):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=40,
+                    help="untimed launches first; the shader clock needs about 25 ms of work to settle after a pause")
     ap.add_argument("--workload", default="sq8192_normal")
     ap.add_argument("--mode", default="f32", choices=["f32", "f16"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
