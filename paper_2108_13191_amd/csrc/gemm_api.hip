@@ -14,8 +14,8 @@ namespace {
 // then two more launch forms of entry 3 for problems with several tiles per compute
 // unit: chained (one workgroup per unit walks its tiles) and staggered (every other
 // unit starts with half a tile); last the 256 x 128 kernel with two accumulator sets
-// (kept for comparison, never selected).
-int num_configs() { return 4 + tiled_num_configs() + 6; }
+// (kept for comparison, never selected), and the 256 x 192 form of entry 3.
+int num_configs() { return 4 + tiled_num_configs() + 7; }
 
 const GemmConfigDesc kGeneric = {
     "generic64x64x32", 64, 64, 32, 4, 32, 32, 2 * 64 * (32 + 8) * 2,
@@ -27,7 +27,7 @@ const GemmConfigDesc* config(int id)
     if (id >= 4 + nt)
         return id == 4 + nt ? pingpong16_config(192, 256) : id == 5 + nt ? pingpong16_config(128, 256)
              : id == 6 + nt ? pingpong16_config(128, 128) : id == 7 + nt ? pingpong16_persistent_config()
-             : id == 8 + nt ? pingpong16_staggered_config() : overlap_config();
+             : id == 8 + nt ? pingpong16_staggered_config() : id == 9 + nt ? overlap_config() : pingpong16_config(256, 192);
     return id == 0 ? &kGeneric : id == 1 ? w4_config() : id == 2 ? pingpong_config() : id == 3 ? pingpong16_config(256, 256) : tiled_config(id - 4);
 }
 
@@ -84,9 +84,12 @@ struct Cand { int id; double eff; int per_cu; };
 // rounds of 192x256 tiles instead of 2.25 of 256x256), 9 = its 128x128 form (two
 // workgroups per compute unit, which hide each other's prologue and epilogue:
 // the choice for problems of a few hundred tiles), 5 = 128x128 and 6 = 64x64 of
-// the plain double-buffered kernel; eff = measured throughput per unit of tile
-// area relative to id 3.
-const Cand kCands[] = {{3, 1.0, 1}, {7, 0.87, 1}, {8, 0.78, 1}, {9, 0.9, 2}, {5, 0.7, 2}, {6, 0.4, 4}};
+// the plain double-buffered kernel, 13 = the 256 x 192 form of id 3 (for N = 768 and
+// the like: per tile area it is as fast as id 3, but a round that fills all compute
+// units runs at a lower clock than one that leaves some idle, so that filling the
+// chip pays less than the round count says -- hence 0.8); eff = measured throughput
+// per unit of tile area relative to id 3.
+const Cand kCands[] = {{3, 1.0, 1}, {7, 0.87, 1}, {8, 0.78, 1}, {13, 0.8, 1}, {9, 0.9, 2}, {5, 0.7, 2}, {6, 0.4, 4}};
 
 // Estimated time of one launch in units of tile area: the rounds the grid needs
 // on 256 compute units times the work of one tile, divided by the

@@ -46,7 +46,7 @@ const GemmConfigDesc* tiled_config(int i);
 
 // gemm_pingpong.hip
 const GemmConfigDesc* pingpong_config();
-const GemmConfigDesc* pingpong16_config(int block_m, int block_n);   // 256x256, 192x256, 128x256 or 128x128
+const GemmConfigDesc* pingpong16_config(int block_m, int block_n);   // 256x256, 192x256, 128x256, 256x192 or 128x128
 const GemmConfigDesc* pingpong16_persistent_config();                 // 256x256, one workgroup per compute unit walks its tiles
 const GemmConfigDesc* pingpong16_staggered_config();                  // 256x256, every other compute unit half a tile ahead
 

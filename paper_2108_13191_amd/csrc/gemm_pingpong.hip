@@ -97,6 +97,22 @@ template <int V> struct IntTag { static constexpr int value = V; };
 // fills the compute units better that way (the wavefront tile is then 96 x 64 /
 // 64 x 64; everything else is unchanged).  BN = its columns: 256, or 128 (wavefront
 // tile 32 columns wide) for the small-problem form 128 x 128.
+// Where 16-byte chunk `chunk` of k row `krow` of a B stage sits within its row.  Rows
+// of 256 or 512 bytes all start at bank 0, so the 4 k rows of a transposing read (and
+// the 16-lane blocks that read k and k + 8 together) are spread by XORing the chunk
+// index with 4 (k%4) + 2 ((k/8)%2).  Rows of 384 bytes (192 columns) start at bank 0
+// and 32 in turn, which already separates k and k + 1; k and k + 2, and k and k + 8,
+// are separated by XORing the chunk's low 3 bits with 2 ((k/2)%2) + 4 ((k/8)%2), so a
+// chunk never leaves its 128-byte group (a 384-byte row has no 16 chunks to XOR over).
+// Both values are even (the two chunks of a 16-column read stay adjacent) and the same
+// for k rows 4, 16 and 32 apart (the reads of a fragment differ by instruction offsets).
+template <int BN>
+__device__ __forceinline__ int b_chunk_position(int chunk, int krow)
+{
+    if constexpr (BN == 192) return (chunk & ~7) | ((chunk & 7) ^ ((((krow >> 1) & 1) << 1) | (((krow >> 3) & 1) << 2)));
+    else                     return chunk ^ (((krow & 3) << 2) | (((krow >> 3) & 1) << 1));
+}
+
 template <int BM, int BN>
 constexpr int pp_lds_bytes() { return 2 * (BM * BK * 2) + 3 * (BK * BN * 2); }     // 160 KB for 256 x 256
 
@@ -147,18 +163,17 @@ __device__ __forceinline__ void pp_tile(const TiledParams& p, const uint32_t sme
         row = (m0 + row < p.M) ? row : p.M - 1 - m0;                 // clamp: loaded, never stored
         return ((uint32_t)row * (uint32_t)p.lda + 8 * a_chunk) * 2;
     };
-    // B half (32 k rows x B_ROW bytes) = 4 * TB wave-wide copies of 1 KB = RPC k rows
-    // each (2 for BN = 256, 4 for BN = 128); copy q = wn + 4t.  Lane i writes (k row
-    // RPC*q + i/CPR, chunk position i%CPR), which must hold logical chunk position
-    // ^ swz(k row), swz = 4*(row%4) + 2*((row/8)%2): the row%4 term spreads the
-    // four k rows of one transposing read over the banks, the (row/8)%2 term those
-    // of the 16-lane blocks that read k and k+8 together (16x16x32 operands).
-    constexpr int CPR = B_ROW / 16, RPC = 64 / CPR;                  // chunks per k row, k rows per copy
-    auto b_krow = [&](int t) -> int { return RPC * (wn + 4 * t) + lane / CPR; };   // within the half
+    // B half (32 k rows x B_ROW bytes) = 4 * TB wave-wide copies of 1 KB; copy q = wn +
+    // 4t.  Lane i writes chunk 64 q + i of the half, i.e. k row (64 q + i) / CPR, chunk
+    // position (64 q + i) % CPR (a copy is 2 k rows for BN = 256, 4 for BN = 128, 2 2/3
+    // for BN = 192), and fetches the logical chunk that b_chunk_position puts there
+    // (the map is its own inverse).
+    constexpr int CPR = B_ROW / 16;                                   // chunks per k row
+    auto b_krow = [&](int t) -> int { return (64 * (wn + 4 * t) + lane) / CPR; };   // within the half
     auto b_offset = [&](int t, int ln) -> uint32_t {                  // relative to the half's first k row
-        const int krow = RPC * (wn + 4 * t) + ln / CPR;
-        const int swz = ((krow & 3) << 2) | (((krow >> 3) & 1) << 1);
-        int col = 8 * ((ln % CPR) ^ swz);
+        const int g = 64 * (wn + 4 * t) + ln;
+        const int krow = g / CPR;
+        int col = 8 * b_chunk_position<BN>(g % CPR, krow);
         if (n0 + col + 8 > p.N) col = 0;                              // clamp: loaded, never stored
         return ((uint32_t)krow * (uint32_t)p.ldb + col) * 2;
     };
@@ -268,11 +283,11 @@ __device__ __forceinline__ void pp_tile(const TiledParams& p, const uint32_t sme
     {
         const int blk = lane_t >> 4, j = lane_t & 15;
         const int krow = (MI == 32) ? 8 * (blk >> 1) + (j >> 2) : 8 * blk + (j >> 2);   // first read; +4 second
-        const int swz = ((krow & 3) << 2) | (((krow >> 3) & 1) << 1);                    // unchanged by +4, +16, +32
 #pragma unroll
         for (int fn = 0; fn < FN; fn++) {
             const int col = wn * WN + fn * MI + ((MI == 32) ? 16 * (blk & 1) : 0) + 4 * (j & 3);   // first of 4 columns
-            b_rd[fn] = smem_base + B_REGION + (uint32_t)krow * B_ROW + (uint32_t)(((col >> 3) ^ swz) * 16 + 2 * (col & 7));
+            // (the position is the same for k rows 4, 16 and 32 further on)
+            b_rd[fn] = smem_base + B_REGION + (uint32_t)krow * B_ROW + (uint32_t)(b_chunk_position<BN>(col >> 3, krow) * 16 + 2 * (col & 7));
         }
     }
 
@@ -313,7 +328,7 @@ __device__ __forceinline__ void pp_tile(const TiledParams& p, const uint32_t sme
     // that the barrier that follows publishes them.
     constexpr int NMFMA = (NSL / 2) * FM * FN;
     constexpr int NPRE = (sizeof(CT) == 2) ? 2 : 1;     // slabs of 32 C rows requested before the last two k steps
-    constexpr int LPR = WN / 4;                         // epilogue: lanes per row segment (4 columns each),
+    constexpr int LPR = (WN == 48) ? 16 : WN / 4;       // epilogue: lanes per row segment (4 columns each; 48 columns: 12 of 16 lanes used),
     constexpr int RPP = 64 / LPR, PASSES = 32 / RPP;    // rows per pass, passes per slab of 32 rows
     // copy_tag: 0 no copies (last two k steps), 1 k step k + 2 is a whole one,
     // 2 it is the k tail
@@ -394,7 +409,7 @@ __device__ __forceinline__ void pp_tile(const TiledParams& p, const uint32_t sme
     // k steps are multiplied (loads complete in order: the waits of those k steps
     // leave exactly these loads outstanding).
     typedef typename CVec4<CT>::type ctx4;
-    constexpr int PITCH = WN * 4 + 16;                       // 272 B for 64 columns
+    constexpr int PITCH = LPR * 16 + 16;                     // 272 B for 64 (and 48) columns
     // (PERSIST: in the second A buffer and the second and third B buffers, which the
     // next tile's k step 0 leaves alone)
     const uint32_t tbuf = !PERSIST ? smem_base + (uint32_t)wave * (32u * PITCH)
@@ -406,7 +421,7 @@ __device__ __forceinline__ void pp_tile(const TiledParams& p, const uint32_t sme
     const uint32_t w_addr = tbuf + (uint32_t)(lane_e & (MI - 1)) * PITCH + (uint32_t)(lane_e / MI) * 16;
     const uint32_t r_addr = tbuf + (uint32_t)(lane_e / LPR) * PITCH + (uint32_t)(lane_e % LPR) * 16;
     const int orow = lane_e / LPR, ocol = 4 * (lane_e % LPR);     // this lane's row (of RPP) and column in a pass
-    const bool col_ok = !edge || (ccol0 + ocol < p.N);         // N is a multiple of 8: all 4 columns or none
+    const bool col_ok = (LPR * 4 == WN || ocol < WN) && (!edge || (ccol0 + ocol < p.N));   // N is a multiple of 8: all 4 columns or none
     CT* const cptr = Cbase + (int64_t)(crow0 + orow) * p.ldc + ccol0 + ocol;
     float bias4[4] = {0.0f, 0.0f, 0.0f, 0.0f};              // fused epilogue: this lane's 4 columns of the bias
     if (p.bias && col_ok) {
@@ -649,6 +664,8 @@ const GemmConfigDesc kPingPong16_192 = {
     "pp192x256x64_w2x4_mi16", 192, 256, BK, 8, 96, 64, lds_pp(192, 256), true, launch_pp<16, 192, 256>, grid_pp<192, 256>};
 const GemmConfigDesc kPingPong16_128 = {
     "pp128x256x64_w2x4_mi16", 128, 256, BK, 8, 64, 64, lds_pp(128, 256), true, launch_pp<16, 128, 256>, grid_pp<128, 256>};
+const GemmConfigDesc kPingPong16_256x192 = {
+    "pp256x192x64_w2x4_mi16", 256, 192, BK, 8, 128, 48, lds_pp(256, 192), true, launch_pp<16, 256, 192>, grid_pp<256, 192>};
 const GemmConfigDesc kPingPong16_128x128 = {
     "pp128x128x64_w2x4_mi16", 128, 128, BK, 8, 64, 32, lds_pp(128, 128), true, launch_pp<16, 128, 128>, grid_pp<128, 128>};
 const GemmConfigDesc kPingPong16Mixed = {
@@ -664,5 +681,6 @@ const GemmConfigDesc* pingpong_config() { return &kPingPong; }
 const GemmConfigDesc* pingpong16_config(int bm, int bn)
 {
     if (bn == 128) return &kPingPong16_128x128;
+    if (bn == 192) return &kPingPong16_256x192;
     return bm == 128 ? &kPingPong16_128 : bm == 192 ? &kPingPong16_192 : &kPingPong16;
 }
