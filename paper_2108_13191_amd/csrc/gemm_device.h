@@ -17,6 +17,7 @@ struct TiledParams {
     int tiles_m, tiles_n, group_m;
     const void* bias;      // fused epilogue: N elements of C's type or nullptr; relu 0 / 1
     int relu;
+    int stagger_ticks;     // chained launch: workgroups on odd XCDs start this many 10 ns ticks late (0: all at once)
 };
 
 // The fused epilogue on one result: + bias, then ReLU written so that NaN and

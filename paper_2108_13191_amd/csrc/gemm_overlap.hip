@@ -411,7 +411,7 @@ int launch_overlap(const GemmArgs& a)
     if (g < 0) return GEMM_F16_ERR_SIZE;
     // k tails and very short k loops: the plain 256 x 256 launch (the selector never sends such problems here)
     if (a.K % BK != 0 || a.K / BK < MIN_KT) return pingpong16_config(256, 256)->launch(a);
-    TiledParams p;
+    TiledParams p = {};
     p.M = (int)a.M; p.N = (int)a.N; p.K = (int)a.K;
     p.A = a.A; p.lda = a.lda; p.B = a.B; p.ldb = a.ldb; p.C = a.C; p.ldc = a.ldc;
     p.bias = a.bias; p.relu = a.relu;

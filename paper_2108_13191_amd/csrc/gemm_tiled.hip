@@ -282,7 +282,7 @@ int launch_tiled(const GemmArgs& a)
 {
     const int64_t g = grid_tiled<BM, BN, WAVES_M, WAVES_N>(a.M, a.N);
     if (g < 0) return GEMM_F16_ERR_SIZE;
-    TiledParams p;
+    TiledParams p = {};
     p.M = (int)a.M; p.N = (int)a.N; p.K = (int)a.K;
     p.A = a.A; p.lda = a.lda; p.B = a.B; p.ldb = a.ldb; p.C = a.C; p.ldc = a.ldc;
     p.bias = a.bias; p.relu = a.relu;

@@ -319,7 +319,7 @@ int launch_w4(const GemmArgs& a)
     const int64_t g = grid_w4(a.M, a.N);
     if (g < 0) return GEMM_F16_ERR_SIZE;
     if (a.bias || a.relu) return GEMM_F16_ERR_CONFIG;      // this comparison kernel has no fused epilogue
-    TiledParams p;
+    TiledParams p = {};
     p.bias = nullptr; p.relu = 0;
     p.M = (int)a.M; p.N = (int)a.N; p.K = (int)a.K;
     p.A = a.A; p.lda = a.lda; p.B = a.B; p.ldb = a.ldb; p.C = a.C; p.ldc = a.ldc;

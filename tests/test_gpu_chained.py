@@ -34,8 +34,9 @@ def _auto_config():
     binding.force_config(-1)
 
 
-# (M, N, K): 552 / 600 / 792 / 520 tiles of 256 x 256
-SHAPES = [(6000, 5704, 200), (6144, 6400, 128), (8440, 5896, 40), (5120, 6656, 64), (6100, 5640, 328)]
+# (M, N, K): 552 / 600 / 792 / 520 / 552 / 1188 tiles of 256 x 256 (three and more per compute unit: the chained
+# form then also starts every other XCD late)
+SHAPES = [(6000, 5704, 200), (6144, 6400, 128), (8440, 5896, 40), (5120, 6656, 64), (6100, 5640, 328), (9000, 8200, 136)]
 
 
 @pytest.mark.parametrize("which", [0, 1])
