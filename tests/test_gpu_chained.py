@@ -103,3 +103,33 @@ def test_fused_epilogue(oracle_mod, which):
     want = oracle_mod.bias_act(Cref, bias, True)
     got = dC.cpu().numpy().astype(np.float64)
     assert np.all(np.abs(got - want) <= 1e-5 * (S + np.abs(C0) + np.abs(bias)[None, :]) + 1e-30)
+
+
+def test_chained_and_late_started_launch_under_hip_graph_capture(oracle_mod):
+    """A problem the selector runs chained with every other XCD started late (three tiles per
+    compute unit, short k loop), captured into a HIP graph: every replay, with eager work in
+    between, adds the same exact product (integer inputs)."""
+    from gpu_util import DevMat
+    M, N, K = 6144, 8192, 128
+    q = binding.query_config(0, M, N, K, 256, K, 256, N, 256, N)
+    assert q["name"].endswith("_chain") and q["grid"] == 256, q
+    A, B, C0 = wl.make_inputs(M, N, K, "int2", "zeros", seed=51)
+    dA, dB, dC = DevMat(A), DevMat(B), DevMat(C0)
+    Cref, _ = oracle_mod.gemm_f16(A, B, C0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                                  # warm-up outside capture, as torch asks
+        binding.check(binding.gemm_f16_f32acc(M, N, K, dA.ptr, dA.ld, dB.ptr, dB.ld, dC.ptr, dC.ld, side.cuda_stream))
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        rc = binding.gemm_f16_f32acc(M, N, K, dA.ptr, dA.ld, dB.ptr, dB.ld, dC.ptr, dC.ld,
+                                     torch.cuda.current_stream().cuda_stream)
+    assert rc == binding.OK
+    torch.cuda.synchronize()
+    for rep in range(2, 5):
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.ones(1 << 20, device="cuda").sum().item() == float(1 << 20)      # eager work between replays
+        assert np.array_equal(dC.fetch(), oracle_mod.round_to_f32(float(rep) * Cref)), f"replay {rep - 1}"
