@@ -514,10 +514,30 @@ __device__ __forceinline__ void pp_tile(const TiledParams& p, const uint32_t sme
     }   // tiles
 }
 
+// Short k loops with several tiles per compute unit: the workgroups that start on
+// every other XCD (consecutive block indices go to the 8 XCDs in turn) begin 10-15 us
+// late and stay that far behind, so that the two halves of the chip read and write C
+// -- which takes all of HBM's bandwidth when every unit does it at once -- at
+// different times.  Whole XCDs are shifted, so each L2 still serves 32 units that walk
+// k in lockstep.  Only the first `first_generation` workgroups wait (those that start
+// when the launch does; the others start as units free up and inherit the offset).
+// The delay is paid once per launch: measured +2 ... +4 % at 3 tiles per unit, +4 ... +10 % at 4-8.
+__device__ __forceinline__ void late_start(const TiledParams& p, int first_generation)
+{
+    if (p.stagger_ticks > 0 && (blockIdx.x & 1) && (int)blockIdx.x < first_generation) {
+        const uint64_t t0 = wall_clock64();             // 100 MHz
+        for (int spins = 0; wall_clock64() - t0 < (uint64_t)p.stagger_ticks && spins < 20000; spins++) __builtin_amdgcn_s_sleep(16);
+    }
+}
+// workgroups that run at once on an MI355X: one per compute unit, two where the LDS allows
+template <int BM, int BN>
+constexpr int pp_first_generation() { return 256 * (pp_lds_bytes<BM, BN>() <= 80 * 1024 ? 2 : 1); }
+
 template <typename CT, int MI, bool TAIL, int BM, int BN>
 __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
 {
     __shared__ __attribute__((aligned(1024))) char smem[pp_lds_bytes<BM, BN>()];
+    late_start(p, pp_first_generation<BM, BN>());
     int tile_m, tile_n;
     tile_of_block(p, blockIdx.x, tile_m, tile_n);
     pp_tile<CT, MI, TAIL, BM, BN>(p, (uint32_t)(uintptr_t)(lds_ptr_t)smem, tile_m * BM, tile_n * BN);
@@ -530,16 +550,7 @@ template <typename CT, int MI, bool TAIL>
 __global__ __launch_bounds__(512) void gemm_pp256_persistent_kernel(const TiledParams p)
 {
     __shared__ __attribute__((aligned(1024))) char smem[pp_lds_bytes<256, 256>()];
-    // Short k loops with several tiles per compute unit: the workgroups of every other
-    // XCD (consecutive block indices go to the 8 XCDs in turn) start 10-15 us late and
-    // stay that far behind, so that the two halves of the chip read and write C -- which
-    // takes all of HBM's bandwidth when every unit does it at once -- at different times.
-    // Whole XCDs are shifted, so each L2 still serves 32 units that walk k in lockstep.
-    // The delay is paid once per launch; measured +2 % at 3 tiles per unit, +10 % at 4-8.
-    if (p.stagger_ticks > 0 && (blockIdx.x & 1)) {
-        const uint64_t t0 = wall_clock64();             // 100 MHz
-        for (int spins = 0; wall_clock64() - t0 < (uint64_t)p.stagger_ticks && spins < 20000; spins++) __builtin_amdgcn_s_sleep(16);
-    }
+    late_start(p, (int)gridDim.x);
     int tile_m, tile_n;
     tile_of_block(p, blockIdx.x, tile_m, tile_n);
     pp_tile<CT, MI, TAIL, 256, 256, true>(p, (uint32_t)(uintptr_t)(lds_ptr_t)smem, tile_m * 256, tile_n * 256,
@@ -594,6 +605,10 @@ int launch_pp(const GemmArgs& a)
     p.tiles_m = (int)((a.M + BM - 1) / BM);
     p.tiles_n = (int)((a.N + BN - 1) / BN);
     p.group_m = 8 < p.tiles_m ? 8 : p.tiles_m;     // an XCD's 32 concurrent tiles form an 8 x 4 block of C
+    // late start of every other XCD (see late_start): short k loops and four or more rounds of workgroups
+    // (measured +4 ... +9 % on every tile form; at three rounds of the 128 x 128 form the delay costs more than it gains)
+    const int64_t at_once = (int64_t)compute_units() * (pp_lds_bytes<BM, BN>() <= 80 * 1024 ? 2 : 1);
+    p.stagger_ticks = (a.K <= 2048 && g >= 4 * at_once) ? 1200 : 0;
     const bool tail = (a.K % BK) != 0;
     if (a.c_is_f16) {
         if (tail) hipLaunchKernelGGL((gemm_pp256_kernel<half_t, MI, true, BM, BN>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
