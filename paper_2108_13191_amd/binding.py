@@ -11,9 +11,27 @@ from __future__ import annotations
 import ctypes
 import os
 
+import contextlib
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgemm_f16.so")
-_lib = None
+# the same library plus the comparison kernels and ablation rows (never selected; reached by
+# forcing their configuration ids, which follow the product's): see build.py
+LADDER_LIB_PATH = os.path.join(_HERE, "libgemm_f16_ladder.so")
+_libs = {}
+_active = "product"
+
+
+@contextlib.contextmanager
+def library(kind: str):
+    """Within the block every function of this module calls into the named build
+    ("product" or "ladder").  The two keep separate forced-configuration state."""
+    global _active
+    prev, _active = _active, kind
+    try:
+        yield
+    finally:
+        _active = prev
 
 OK = 0
 ERR_SIZE, ERR_PITCH, ERR_NULL, ERR_LAUNCH, ERR_CONFIG, ERR_ALIGN = -1, -2, -3, -4, -5, -6
@@ -38,14 +56,14 @@ class GemmError(RuntimeError):
 
 
 def load() -> ctypes.CDLL:
-    """Load libgemm_f16.so (built in-tree); raise if it is missing."""
-    global _lib
-    if _lib is None:
-        if not os.path.exists(LIB_PATH):
+    """Load the active library (built in-tree); raise if it is missing."""
+    if _active not in _libs:
+        path = {"product": LIB_PATH, "ladder": LADDER_LIB_PATH}[_active]
+        if not os.path.exists(path):
             raise ImportError(
-                f"{LIB_PATH} is missing: build the HIP library first "
+                f"{path} is missing: build the HIP library first "
                 "(python -m paper_2108_13191_amd.build); there is no CPU fallback")
-        lib = ctypes.CDLL(LIB_PATH)
+        lib = ctypes.CDLL(path)
         i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
         for name in ("gemm_f16_f32acc", "gemm_f16_f16acc"):
             f = getattr(lib, name)
@@ -66,8 +84,8 @@ def load() -> ctypes.CDLL:
         lib.gemm_f16_describe_config.restype = ci
         lib.gemm_f16_force_config.argtypes = [ci]
         lib.gemm_f16_force_config.restype = ci
-        _lib = lib
-    return _lib
+        _libs[_active] = lib
+    return _libs[_active]
 
 
 def _ptr(x) -> int:

@@ -7,49 +7,84 @@
 
 namespace {
 
-// Configuration table: entry 0 is the any-shape kernel, entry 1 the 256 x 256
-// four-wavefront kernel, entries 2 and 3 the 256 x 256 phase-alternating
-// eight-wavefront kernel on 32x32x16 and on 16x16x32 MFMAs, then the generic
-// double-buffered tiles, then the 192 x 256, 128 x 256 and 128 x 128 forms of entry 3,
-// then two more launch forms of entry 3 for problems with several tiles per compute
-// unit: chained (one workgroup per unit walks its tiles) and staggered (every other
-// unit starts with half a tile); last the 256 x 128 kernel with two accumulator sets
-// (kept for comparison, never selected), and the 256 x 192 form of entry 3.
-int num_configs() { return 4 + tiled_num_configs() + 7; }
+// Configuration table.  The product library holds the any-shape kernel, the phase-alternating
+// eight-wavefront kernel (16x16x32 MFMA) in its five tile shapes and its two launch forms for
+// several tiles per compute unit (chained, staggered), and the plain ring-buffered 64 x 64 tiling
+// for the smallest problems.  A ladder build (GEMM_F16_LADDER, libgemm_f16_ladder.so) appends
+// the comparison kernels and ablation rows behind them; the selector never picks those.
+enum {
+    ID_GENERIC = 0,
+    ID_PP256,          // 256 x 256
+    ID_PP192,          // 192 x 256
+    ID_PP128,          // 128 x 256
+    ID_PP256x192,      // 256 x 192
+    ID_PP128x128,      // 128 x 128, two workgroups per compute unit
+    ID_CHAIN,          // 256 x 256, one workgroup per compute unit walks its tiles
+    ID_STAG,           // 256 x 256, every other compute unit starts on half a tile
+    ID_T64,            // 64 x 64, four LDS stages
+    NUM_PRODUCT
+};
 
 const GemmConfigDesc kGeneric = {
     "generic64x64x32", 64, 64, 32, 4, 32, 32, 2 * 64 * (32 + 8) * 2,
     false, launch_generic, grid_generic};
 
+#ifdef GEMM_F16_LADDER
+constexpr int NUM_LADDER = 9;
+#else
+constexpr int NUM_LADDER = 0;
+#endif
+int num_configs() { return NUM_PRODUCT + NUM_LADDER; }
+
 const GemmConfigDesc* config(int id)
 {
-    const int nt = tiled_num_configs();
-    if (id >= 4 + nt)
-        return id == 4 + nt ? pingpong16_config(192, 256) : id == 5 + nt ? pingpong16_config(128, 256)
-             : id == 6 + nt ? pingpong16_config(128, 128) : id == 7 + nt ? pingpong16_persistent_config()
-             : id == 8 + nt ? pingpong16_staggered_config() : id == 9 + nt ? overlap_config() : pingpong16_config(256, 192);
-    return id == 0 ? &kGeneric : id == 1 ? w4_config() : id == 2 ? pingpong_config() : id == 3 ? pingpong16_config(256, 256) : tiled_config(id - 4);
+    switch (id) {
+    case ID_GENERIC:   return &kGeneric;
+    case ID_PP256:     return pingpong16_config(256, 256);
+    case ID_PP192:     return pingpong16_config(192, 256);
+    case ID_PP128:     return pingpong16_config(128, 256);
+    case ID_PP256x192: return pingpong16_config(256, 192);
+    case ID_PP128x128: return pingpong16_config(128, 128);
+    case ID_CHAIN:     return pingpong16_persistent_config();
+    case ID_STAG:      return pingpong16_staggered_config();
+    case ID_T64:       return tiled_config(64);
+#ifdef GEMM_F16_LADDER
+    case NUM_PRODUCT + 0: return tiled_config(128);
+    case NUM_PRODUCT + 1: return tiled_config(256);
+    case NUM_PRODUCT + 2: return tiled_no_swizzle_config();
+    case NUM_PRODUCT + 3: return pingpong_config();
+    case NUM_PRODUCT + 4: return pingpong16_no_xcd_order_config();
+    case NUM_PRODUCT + 5: return w4_config();
+    case NUM_PRODUCT + 6: return overlap_config();
+    case NUM_PRODUCT + 7: return interleaved_config();
+    case NUM_PRODUCT + 8: return generic_c_in_loop_config();
+#endif
+    default: return &kGeneric;
+    }
 }
 
 int g_forced = -1;
 
 }  // namespace
 
-// Compute units of the current device; the persistent kernels launch one workgroup
-// per unit.  The same on every call; a data race on the cached value is benign.
-int compute_units()
+const ChipShape& chip()
 {
-    static int n = 0;
-    if (n == 0) {
+    static const ChipShape shape = [] {
+        ChipShape c = {256, 8, 100000};
         int dev = 0, v = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
-        n = v;
-    }
-    return n;
+        if (hipGetDevice(&dev) == hipSuccess) {
+            if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) {
+                c.cus = v;
+                c.xcds = v >= 32 ? v / 32 : 1;
+            }
+            if (hipDeviceGetAttribute(&v, hipDeviceAttributeWallClockRate, dev) == hipSuccess && v > 0) c.wall_clock_khz = v;
+        }
+        return c;
+    }();
+    return shape;
 }
 
 namespace {
-
 
 int check_args(int c_is_f16, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
                const void* B, int64_t ldb, const void* C, int64_t ldc)
@@ -64,12 +99,16 @@ int check_args(int c_is_f16, int64_t M, int64_t N, int64_t K, const void* A, int
     return GEMM_F16_OK;
 }
 
-bool aligned_for_tiled(int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb)
+// Pitches above this take the any-shape kernel, whose addresses are all 64-bit: the tuned
+// kernels keep tile-relative byte offsets of A and B (up to 256 rows) in 32 bits, and the
+// plain tilings (64 x 64 and the ladder's larger ones) do the same for C.
+constexpr int64_t MAX_TUNED_PITCH = 1 << 22;
+
+bool aligned_for_tiled(int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, int64_t ldc)
 {
     return ((uintptr_t)A % 16 == 0) && ((uintptr_t)B % 16 == 0) && lda % 8 == 0 && ldb % 8 == 0 &&
            K % 8 == 0 && N % 8 == 0 && K >= 8 &&
-           // tile-relative byte offsets (up to 256 rows) are kept in 32 bits
-           lda <= (1 << 22) && ldb <= (1 << 22);
+           lda <= MAX_TUNED_PITCH && ldb <= MAX_TUNED_PITCH && ldc <= MAX_TUNED_PITCH;
 }
 
 // What a call runs: one configuration on all rows, or the 256 x 256 kernel on
@@ -78,21 +117,18 @@ bool aligned_for_tiled(int64_t N, int64_t K, const void* A, int64_t lda, const v
 struct Plan { int id; int64_t rows1; int id2; };
 
 struct Cand { int id; double eff; int per_cu; };
-// ids: 3 = 256x256 (eight wavefronts, phase-alternating, 16x16x32 MFMA: measured
-// faster than the 32x32x16 form of the same kernel, id 2), 7 and 8 = its 192- and
-// 128-row forms (less operand reuse per tile, but e.g. 6144^3 is exactly three
-// rounds of 192x256 tiles instead of 2.25 of 256x256), 9 = its 128x128 form (two
-// workgroups per compute unit, which hide each other's prologue and epilogue:
-// the choice for problems of a few hundred tiles), 5 = 128x128 and 6 = 64x64 of
-// the plain double-buffered kernel, 13 = the 256 x 192 form of id 3 (for N = 768 and
-// the like: per tile area it is as fast as id 3, but a round that fills all compute
-// units runs at a lower clock than one that leaves some idle, so that filling the
-// chip pays less than the round count says -- hence 0.8); eff = measured throughput
-// per unit of tile area relative to id 3.
-const Cand kCands[] = {{3, 1.0, 1}, {7, 0.87, 1}, {8, 0.78, 1}, {13, 0.8, 1}, {9, 0.9, 2}, {5, 0.7, 2}, {6, 0.4, 4}};
+// The 192- and 128-row forms reuse operands less per tile, but e.g. 6144^3 is exactly three
+// rounds of 192 x 256 tiles instead of 2.25 of 256 x 256.  The 128 x 128 form runs two
+// workgroups per compute unit, which hide each other's prologue and epilogue: the choice for
+// problems of a few hundred tiles.  256 x 192 serves N = 768 and the like: per tile area it is
+// as fast as 256 x 256, but a round that fills all compute units runs at a lower clock than one
+// that leaves some idle, so that filling the chip pays less than the round count says -- hence
+// 0.8.  eff = measured throughput per unit of tile area relative to the 256 x 256 tile.
+const Cand kCands[] = {{ID_PP256, 1.0, 1}, {ID_PP192, 0.87, 1}, {ID_PP128, 0.78, 1}, {ID_PP256x192, 0.8, 1},
+                       {ID_PP128x128, 0.9, 2}, {ID_T64, 0.4, 4}};
 
 // Estimated time of one launch in units of tile area: the rounds the grid needs
-// on 256 compute units times the work of one tile, divided by the
+// on the device's compute units times the work of one tile, divided by the
 // configuration's efficiency (large tiles reuse operands better; small tiles
 // fill the chip on small problems -- the trade-off the paper reports in
 // section Mixed Precision Performance).  A partial round costs a full one,
@@ -106,17 +142,17 @@ double launch_cost(const Cand& c, int64_t M, int64_t N, int64_t K)
     const int64_t g = d->grid(M, N);
     if (g < 0) return -1.0;
     double eff = c.eff;
-    if (c.id == 9) { eff = 0.78 + 0.2 * (K < 1024 ? 1.0 : 1024.0 / (double)K); if (eff > 0.92) eff = 0.92; }
-    const int64_t slots = 256 * c.per_cu;
+    if (c.id == ID_PP128x128) { eff = 0.78 + 0.2 * (K < 1024 ? 1.0 : 1024.0 / (double)K); if (eff > 0.92) eff = 0.92; }
+    const int64_t cus = chip().cus, slots = cus * c.per_cu;
     const int64_t full = g / slots, left = g % slots;
-    const double sharing = (double)((left + 255) / 256);                       // workgroups per compute unit in the last round
+    const double sharing = (double)((left + cus - 1) / cus);                   // workgroups per compute unit in the last round
     const double last = left ? (0.5 + 0.5 * sharing / c.per_cu) * c.per_cu : 0.0;
     return ((double)full * c.per_cu + last) * (double)d->block_m * d->block_n / eff;
 }
 
 int best_single(int64_t M, int64_t N, int64_t K, double* cost_out)
 {
-    int best = 3;
+    int best = ID_PP256;
     double best_cost = -1.0;
     for (const Cand& c : kCands) {
         const double cost = launch_cost(c, M, N, K);
@@ -132,9 +168,8 @@ int best_single(int64_t M, int64_t N, int64_t K, double* cost_out)
 // configuration suits the left-over rows best behind them -- 5120^3 is one full
 // round of 256 x 256 tiles plus one round of 192 x 256 tiles instead of two
 // rounds of which the second is 56 % full.
-constexpr int ID_PP256 = 3;
-int id_chained() { return 4 + tiled_num_configs() + 3; }
-int id_staggered() { return 4 + tiled_num_configs() + 4; }
+int id_chained() { return ID_CHAIN; }
+int id_staggered() { return ID_STAG; }
 
 // The 256 x 256 tiling runs chained when a compute unit gets more than one tile
 // (measured 1-5 % faster, more the shorter the k loop; the k-tail form is not:
@@ -146,39 +181,39 @@ int chained_if_it_pays(int id, int64_t rows, int64_t N, int64_t K)
     return c->grid(rows, N) < config(ID_PP256)->grid(rows, N) ? id_chained() : id;
 }
 
-Plan select_plan_unchained(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb)
+Plan select_plan_unchained(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, int64_t ldc)
 {
-    if (!aligned_for_tiled(N, K, A, lda, B, ldb)) return {0, M, -1};
+    if (!aligned_for_tiled(N, K, A, lda, B, ldb, ldc)) return {ID_GENERIC, M, -1};
     if (g_forced >= 0 && g_forced < num_configs()) return {g_forced, M, -1};
     double cost = 0;
     Plan best = {best_single(M, N, K, &cost), M, -1};
-    const int64_t tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
-    if (tiles_n > 256 || tiles_m < 2 || cost < 0) return best;
+    const int64_t tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256, cus = chip().cus;
+    if (tiles_n > cus || tiles_m < 2 || cost < 0) return best;
     // Short k loops, two or more full rounds of 256 x 256 tiles and a last round at
     // most half full: the staggered form fills that round with half tiles (and
     // spreads the C traffic, which dominates such problems, over time).  With long
     // k loops the two halves of the chip would no longer share operand panels in L2.
     {
-        const int64_t tiles = tiles_m * tiles_n, full = tiles / 256, left = tiles % 256;
+        const int64_t tiles = tiles_m * tiles_n, full = tiles / cus, left = tiles % cus;
         const double staggered = ((double)full + 0.55) * 65536.0;
-        if (K <= 1024 && full >= 2 && left > 0 && left <= 128 && staggered < cost) { cost = staggered; best = {id_staggered(), M, -1}; }
+        if (cus == 256 && K <= 1024 && full >= 2 && left > 0 && left <= 128 && staggered < cost) { cost = staggered; best = {id_staggered(), M, -1}; }
     }
     const double second_launch = 3000.0;                  // drain and refill between the two launches
-    const int64_t total_rounds = (tiles_m * tiles_n + 255) / 256;
+    const int64_t total_rounds = (tiles_m * tiles_n + cus - 1) / cus;
     for (int64_t r = total_rounds > 4 ? total_rounds - 3 : 1; r <= total_rounds; r++) {   // the cut is near the end
-        const int64_t j = (r * 256) / tiles_n;             // tile rows that fit r rounds
+        const int64_t j = (r * cus) / tiles_n;             // tile rows that fit r rounds
         if (j < 1 || j >= tiles_m) continue;
         double rest = 0;
         const int id2 = best_single(M - 256 * j, N, K, &rest);
-        const double first = (double)((j * tiles_n + 255) / 256) * 65536.0;
+        const double first = (double)((j * tiles_n + cus - 1) / cus) * 65536.0;
         if (rest >= 0 && first + rest + second_launch < cost) { cost = first + rest + second_launch; best = {ID_PP256, 256 * j, id2}; }
     }
     return best;
 }
 
-Plan select_plan(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb)
+Plan select_plan(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, int64_t ldc)
 {
-    Plan pl = select_plan_unchained(M, N, K, A, lda, B, ldb);
+    Plan pl = select_plan_unchained(M, N, K, A, lda, B, ldb, ldc);
     if (g_forced >= 0 && g_forced < num_configs()) return pl;        // a forced configuration runs as it is
     pl.id = chained_if_it_pays(pl.id, pl.rows1, N, K);
     if (pl.id2 >= 0) pl.id2 = chained_if_it_pays(pl.id2, M - pl.rows1, N, K);
@@ -215,9 +250,9 @@ int run(int c_is_f16, int64_t M, int64_t N, int64_t K, const void* A, int64_t ld
         a.M = M; a.N = N; a.K = 0;
         a.A = (const half_t*)A; a.lda = lda; a.B = (const half_t*)B; a.ldb = ldb; a.C = C; a.ldc = ldc;
         a.c_is_f16 = c_is_f16; a.stream = (hipStream_t)stream;
-        return config(0)->launch(a);
+        return config(ID_GENERIC)->launch(a);
     }
-    const Plan plan = select_plan(M, N, K, A, lda, B, ldb);
+    const Plan plan = select_plan(M, N, K, A, lda, B, ldb, ldc);
     a.M = plan.rows1; a.N = N; a.K = K;
     a.A = (const half_t*)A; a.lda = lda; a.B = (const half_t*)B; a.ldb = ldb; a.C = C; a.ldc = ldc;
     a.c_is_f16 = c_is_f16; a.stream = (hipStream_t)stream;
@@ -283,7 +318,7 @@ int gemm_f16_query_config(int c_is_f16, int64_t M, int64_t N, int64_t K, const v
     const void* c = C ? C : (const void*)16;
     const int rc = check_args(c_is_f16, M, N, K, a, lda, b, ldb, c, ldc);
     if (rc != GEMM_F16_OK) return rc;
-    const Plan plan = select_plan(M, N, K, a, lda, b, ldb);
+    const Plan plan = select_plan(M, N, K, a, lda, b, ldb, ldc);
     if (M == 0 || N == 0 || K == 0) { fill_desc(plan.id, 0, out); return GEMM_F16_OK; }
     int64_t g = config(plan.id)->grid(plan.rows1, N);
     if (g < 0) return GEMM_F16_ERR_SIZE;

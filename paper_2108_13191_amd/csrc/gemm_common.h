@@ -36,25 +36,36 @@ struct GemmConfigDesc {
     int64_t (*grid)(int64_t M, int64_t N);    // workgroups for a problem (<0: too many)
 };
 
+// What the launchers and the selector assume about the device, in one place: compute units,
+// XCDs (each with its own L2; consecutive workgroup ids are dealt to them in turn), and
+// the rate of the constant wall clock the late start counts in.  Queried once per process
+// from the current device; without a device the MI355X values (256, 8, 100 MHz).
+struct ChipShape {
+    int cus;                // compute units: workgroups of the largest tile that run at once
+    int xcds;               // 32 compute units each on gfx950 parts (8 on an MI355X, fewer in partitioned modes)
+    int wall_clock_khz;
+};
+const ChipShape& chip();                     // gemm_api.hip
+
 // gemm_generic.hip
 int launch_generic(const GemmArgs& a);
 int64_t grid_generic(int64_t M, int64_t N);
 
-// gemm_tiled.hip
-int tiled_num_configs();
-const GemmConfigDesc* tiled_config(int i);
+// gemm_tiled.hip: the plain ring-buffered tiling, 64 x 64 (ladder builds also 128 x 128 and 256 x 256)
+const GemmConfigDesc* tiled_config(int block);
 
 // gemm_pingpong.hip
-const GemmConfigDesc* pingpong_config();
 const GemmConfigDesc* pingpong16_config(int block_m, int block_n);   // 256x256, 192x256, 128x256, 256x192 or 128x128
 const GemmConfigDesc* pingpong16_persistent_config();                 // 256x256, one workgroup per compute unit walks its tiles
 const GemmConfigDesc* pingpong16_staggered_config();                  // 256x256, every other compute unit half a tile ahead
 
-// gemm_overlap.hip
-const GemmConfigDesc* overlap_config();                              // 256x128, two accumulator sets: C traffic under the next tile's MFMAs
-
-// gemm_api.hip
-int compute_units();                                                 // of the current device (256 if there is none)
-
-// gemm_w4.hip
-const GemmConfigDesc* w4_config();
+#ifdef GEMM_F16_LADDER
+// Comparison kernels and ablation rows: built into libgemm_f16_ladder.so only, never selected.
+const GemmConfigDesc* pingpong_config();                             // gemm_pingpong.hip: 256x256 on 32x32x16 MFMAs
+const GemmConfigDesc* pingpong16_no_xcd_order_config();              // gemm_pingpong.hip: tiles dealt to XCDs as the hardware deals workgroups
+const GemmConfigDesc* tiled_no_swizzle_config();                     // gemm_tiled.hip: 256x256, LDS image not swizzled
+const GemmConfigDesc* generic_c_in_loop_config();                    // gemm_generic.hip: C read and written in every k step
+const GemmConfigDesc* interleaved_config();                          // ladder/gemm_interleaved.hip
+const GemmConfigDesc* overlap_config();                              // ladder/gemm_overlap.hip
+const GemmConfigDesc* w4_config();                                   // ladder/gemm_w4.hip
+#endif

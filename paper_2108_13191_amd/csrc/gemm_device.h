@@ -7,7 +7,6 @@
 namespace gemm_dev {
 
 constexpr int BK = 64;             // k extent per LDS stage (f16 elements)
-constexpr int NUM_XCD = 8;
 
 struct TiledParams {
     int M, N, K;
@@ -15,10 +14,28 @@ struct TiledParams {
     const half_t* B; int64_t ldb;
     void* C; int64_t ldc;
     int tiles_m, tiles_n, group_m;
+    int num_xcd;           // XCDs the workgroup ids are dealt to in turn (1: tiles in plain order)
     const void* bias;      // fused epilogue: N elements of C's type or nullptr; relu 0 / 1
     int relu;
-    int stagger_ticks;     // chained launch: workgroups on odd XCDs start this many 10 ns ticks late (0: all at once)
+    int stagger_ticks;     // late start: workgroups on odd XCDs start this many wall-clock ticks late (0: all at once)
+    int first_generation;  // late start: workgroups that begin with the launch (only these wait)
 };
+
+// The fields every launcher fills the same way: the problem, the tile grid for bm x bn tiles,
+// and the tile order (group_m tile rows at a time; an XCD's 32 concurrent tiles should form a
+// near-square block of C).
+inline TiledParams make_tiled_params(const GemmArgs& a, int bm, int bn, int group_m)
+{
+    TiledParams p = {};
+    p.M = (int)a.M; p.N = (int)a.N; p.K = (int)a.K;
+    p.A = a.A; p.lda = a.lda; p.B = a.B; p.ldb = a.ldb; p.C = a.C; p.ldc = a.ldc;
+    p.bias = a.bias; p.relu = a.relu;
+    p.tiles_m = (int)((a.M + bm - 1) / bm);
+    p.tiles_n = (int)((a.N + bn - 1) / bn);
+    p.group_m = group_m < p.tiles_m ? group_m : p.tiles_m;
+    p.num_xcd = chip().xcds;
+    return p;
+}
 
 // The fused epilogue on one result: + bias, then ReLU written so that NaN and
 // -0 pass through.
@@ -64,9 +81,9 @@ __device__ __forceinline__ half4 lds_read_tr16(uint32_t addr)
 __device__ __forceinline__ void tile_of_block(const TiledParams& p, int pid, int& tile_m, int& tile_n)
 {
     const int num = p.tiles_m * p.tiles_n;
-    const int q = num / NUM_XCD, r = num % NUM_XCD;
-    const int x = pid % NUM_XCD;
-    const int l = x * q + (x < r ? x : r) + pid / NUM_XCD;
+    const int q = num / p.num_xcd, r = num % p.num_xcd;
+    const int x = pid % p.num_xcd;
+    const int l = x * q + (x < r ? x : r) + pid / p.num_xcd;
     const int group_size = p.group_m * p.tiles_n;
     const int g = l / group_size;
     const int first_m = g * p.group_m;

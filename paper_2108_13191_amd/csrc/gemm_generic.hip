@@ -11,7 +11,11 @@ namespace {
 
 constexpr int GBM = 64, GBN = 64, GBK = 32, GPAD = 8;
 
-template <typename CT>
+// C_IN_LOOP (a ladder row, never selected): the accumulator goes to C and comes back in every
+// k step, as in the paper's Algorithm "Two-level tiled tensor core Matmul" before the load and
+// store of C are hoisted out of the k loop (section "Generating WMMA Ops and More").  With f16
+// C that rounds the running sum at every step, so the row is built for f32 C only.
+template <typename CT, bool C_IN_LOOP = false>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(
     int M, int N, int K, const half_t* __restrict__ A, int64_t lda,
     const half_t* __restrict__ B, int64_t ldb, CT* __restrict__ C, int64_t ldc, int tiles_n,
@@ -59,6 +63,19 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
             acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc, 0, 0, 0);
         }
         __syncthreads();
+        if constexpr (C_IN_LOOP) {
+            if (k0 + GBK < K) {
+#pragma unroll
+                for (int i = 0; i < 16; i++) {
+                    const int64_t row = m0 + wm * 32 + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
+                    if (row < M && col < N) {
+                        volatile CT* c = &C[row * ldc + col];
+                        *c = (CT)acc[i];
+                        acc[i] = (float)*c;
+                    }
+                }
+            }
+        }
     }
 
     const float bv = (bias && col < N) ? (float)bias[col] : 0.0f;     // fused epilogue: + bias, ReLU (NaN, -0 pass)
@@ -81,16 +98,32 @@ int64_t grid_generic(int64_t M, int64_t N)
     return tm * tn;
 }
 
+#ifdef GEMM_F16_LADDER
+int launch_generic_c_in_loop(const GemmArgs& a)
+{
+    if (a.c_is_f16) return launch_generic(a);
+    const int64_t g = grid_generic(a.M, a.N);
+    if (g < 0) return GEMM_F16_ERR_SIZE;
+    const int tiles_n = (int)((a.N + GBN - 1) / GBN);
+    hipLaunchKernelGGL((gemm_generic_kernel<float, true>), dim3((unsigned)g), dim3(256), 0, a.stream,
+                       (int)a.M, (int)a.N, (int)a.K, a.A, a.lda, a.B, a.ldb, (float*)a.C, a.ldc, tiles_n, (const float*)a.bias, a.relu);
+    return hipGetLastError() == hipSuccess ? GEMM_F16_OK : GEMM_F16_ERR_LAUNCH;
+}
+const GemmConfigDesc kGenericCInLoop = {
+    "generic64x64x32_c_in_loop", 64, 64, 32, 4, 32, 32, 2 * 64 * (32 + 8) * 2, false, launch_generic_c_in_loop, grid_generic};
+const GemmConfigDesc* generic_c_in_loop_config() { return &kGenericCInLoop; }
+#endif
+
 int launch_generic(const GemmArgs& a)
 {
     const int64_t g = grid_generic(a.M, a.N);
     if (g < 0) return GEMM_F16_ERR_SIZE;
     const int tiles_n = (int)((a.N + GBN - 1) / GBN);
     if (a.c_is_f16)
-        hipLaunchKernelGGL(gemm_generic_kernel<half_t>, dim3((unsigned)g), dim3(256), 0, a.stream,
+        hipLaunchKernelGGL((gemm_generic_kernel<half_t>), dim3((unsigned)g), dim3(256), 0, a.stream,
                            (int)a.M, (int)a.N, (int)a.K, a.A, a.lda, a.B, a.ldb, (half_t*)a.C, a.ldc, tiles_n, (const half_t*)a.bias, a.relu);
     else
-        hipLaunchKernelGGL(gemm_generic_kernel<float>, dim3((unsigned)g), dim3(256), 0, a.stream,
+        hipLaunchKernelGGL((gemm_generic_kernel<float>), dim3((unsigned)g), dim3(256), 0, a.stream,
                            (int)a.M, (int)a.N, (int)a.K, a.A, a.lda, a.B, a.ldb, (float*)a.C, a.ldc, tiles_n, (const float*)a.bias, a.relu);
     return hipGetLastError() == hipSuccess ? GEMM_F16_OK : GEMM_F16_ERR_LAUNCH;
 }

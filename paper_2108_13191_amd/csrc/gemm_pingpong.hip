@@ -515,29 +515,39 @@ __device__ __forceinline__ void pp_tile(const TiledParams& p, const uint32_t sme
 }
 
 // Short k loops with several tiles per compute unit: the workgroups that start on
-// every other XCD (consecutive block indices go to the 8 XCDs in turn) begin 10-15 us
-// late and stay that far behind, so that the two halves of the chip read and write C
-// -- which takes all of HBM's bandwidth when every unit does it at once -- at
-// different times.  Whole XCDs are shifted, so each L2 still serves 32 units that walk
-// k in lockstep.  Only the first `first_generation` workgroups wait (those that start
-// when the launch does; the others start as units free up and inherit the offset).
-// The delay is paid once per launch: measured +2 ... +4 % at 3 tiles per unit, +4 ... +10 % at 4-8.
-__device__ __forceinline__ void late_start(const TiledParams& p, int first_generation)
+// every other XCD (consecutive block indices go to the XCDs in turn, so with an even
+// number of XCDs odd indices are odd XCDs) begin 10-15 us late and stay that far behind,
+// so that the two halves of the chip read and write C -- which takes all of HBM's
+// bandwidth when every unit does it at once -- at different times.  Whole XCDs are
+// shifted, so each L2 still serves units that walk k in lockstep.  Only the first
+// p.first_generation workgroups wait (those that start when the launch does; the others
+// start as units free up and inherit the offset).  The delay is paid once per launch:
+// measured +2 ... +4 % at 3 tiles per unit, +4 ... +10 % at 4-8.  The wait is bounded (it
+// ends after 20 000 polls whatever the clock says) and changes no result.
+__device__ __forceinline__ void late_start(const TiledParams& p)
 {
-    if (p.stagger_ticks > 0 && (blockIdx.x & 1) && (int)blockIdx.x < first_generation) {
-        const uint64_t t0 = wall_clock64();             // 100 MHz
+    if (p.stagger_ticks > 0 && (blockIdx.x & 1) && (int)blockIdx.x < p.first_generation) {
+        const uint64_t t0 = wall_clock64();
         for (int spins = 0; wall_clock64() - t0 < (uint64_t)p.stagger_ticks && spins < 20000; spins++) __builtin_amdgcn_s_sleep(16);
     }
 }
-// workgroups that run at once on an MI355X: one per compute unit, two where the LDS allows
+// Host side: the delay in wall-clock ticks, or 0 where the late start does not apply -- the
+// device must deal workgroups to an even number (two or more) of XCDs.
+inline int late_start_ticks()
+{
+    const ChipShape& c = chip();
+    if (c.xcds < 2 || (c.xcds & 1)) return 0;
+    return (int)(12e-6 * 1e3 * c.wall_clock_khz);          // 12 us
+}
+// workgroups that run at once: one per compute unit, two where the LDS allows
 template <int BM, int BN>
-constexpr int pp_first_generation() { return 256 * (pp_lds_bytes<BM, BN>() <= 80 * 1024 ? 2 : 1); }
+int pp_at_once() { return chip().cus * (pp_lds_bytes<BM, BN>() <= 80 * 1024 ? 2 : 1); }
 
 template <typename CT, int MI, bool TAIL, int BM, int BN>
 __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
 {
     __shared__ __attribute__((aligned(1024))) char smem[pp_lds_bytes<BM, BN>()];
-    late_start(p, pp_first_generation<BM, BN>());
+    late_start(p);
     int tile_m, tile_n;
     tile_of_block(p, blockIdx.x, tile_m, tile_n);
     pp_tile<CT, MI, TAIL, BM, BN>(p, (uint32_t)(uintptr_t)(lds_ptr_t)smem, tile_m * BM, tile_n * BN);
@@ -550,7 +560,7 @@ template <typename CT, int MI, bool TAIL>
 __global__ __launch_bounds__(512) void gemm_pp256_persistent_kernel(const TiledParams p)
 {
     __shared__ __attribute__((aligned(1024))) char smem[pp_lds_bytes<256, 256>()];
-    late_start(p, (int)gridDim.x);
+    late_start(p);
     int tile_m, tile_n;
     tile_of_block(p, blockIdx.x, tile_m, tile_n);
     pp_tile<CT, MI, TAIL, 256, 256, true>(p, (uint32_t)(uintptr_t)(lds_ptr_t)smem, tile_m * 256, tile_n * 256,
@@ -573,8 +583,8 @@ __global__ __launch_bounds__(512) void gemm_pp_mixed_kernel(const TiledParams p)
     const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_ptr_t)smem;
     const int tiles = p.tiles_m * p.tiles_n;
     int b = blockIdx.x, half = -1;
-    if (b >= tiles) { const int r = b - tiles; b = ((r >> 5) << 6) | 32 | (r & 31); half = 1; }   // r-th block of the first 256 with bit 5 set
-    else if (b < 256 && (b & 32)) half = 0;
+    if (b >= tiles) { const int r = b - tiles; b = ((r >> 5) << 6) | 32 | (r & 31); half = 1; }   // r-th block of the first generation with bit 5 set
+    else if (b < p.first_generation && (b & 32)) half = 0;
     int tile_m, tile_n;
     tile_of_block(p, b, tile_m, tile_n);
     if (half < 0) {
@@ -594,21 +604,16 @@ int64_t grid_pp(int64_t M, int64_t N)
 }
 
 template <int MI, int BM, int BN>
-int launch_pp(const GemmArgs& a)
+int launch_pp(const GemmArgs& a, bool xcd_order = true)
 {
     const int64_t g = grid_pp<BM, BN>(a.M, a.N);
     if (g < 0) return GEMM_F16_ERR_SIZE;
-    TiledParams p = {};
-    p.M = (int)a.M; p.N = (int)a.N; p.K = (int)a.K;
-    p.A = a.A; p.lda = a.lda; p.B = a.B; p.ldb = a.ldb; p.C = a.C; p.ldc = a.ldc;
-    p.bias = a.bias; p.relu = a.relu;
-    p.tiles_m = (int)((a.M + BM - 1) / BM);
-    p.tiles_n = (int)((a.N + BN - 1) / BN);
-    p.group_m = 8 < p.tiles_m ? 8 : p.tiles_m;     // an XCD's 32 concurrent tiles form an 8 x 4 block of C
+    TiledParams p = make_tiled_params(a, BM, BN, 8);       // an XCD's 32 concurrent tiles form an 8 x 4 block of C
+    if (!xcd_order) p.num_xcd = 1;
     // late start of every other XCD (see late_start): short k loops and four or more rounds of workgroups
     // (measured +4 ... +9 % on every tile form; at three rounds of the 128 x 128 form the delay costs more than it gains)
-    const int64_t at_once = (int64_t)compute_units() * (pp_lds_bytes<BM, BN>() <= 80 * 1024 ? 2 : 1);
-    p.stagger_ticks = (a.K <= 2048 && g >= 4 * at_once) ? 1200 : 0;
+    p.first_generation = pp_at_once<BM, BN>();
+    p.stagger_ticks = (a.K <= 2048 && g >= 4 * (int64_t)p.first_generation) ? late_start_ticks() : 0;
     const bool tail = (a.K % BK) != 0;
     if (a.c_is_f16) {
         if (tail) hipLaunchKernelGGL((gemm_pp256_kernel<half_t, MI, true, BM, BN>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
@@ -619,26 +624,27 @@ int launch_pp(const GemmArgs& a)
     }
     return hipGetLastError() == hipSuccess ? GEMM_F16_OK : GEMM_F16_ERR_LAUNCH;
 }
+template <int MI, int BM, int BN> int launch_pp_plain(const GemmArgs& a) { return launch_pp<MI, BM, BN>(a); }
 
-// fewer than two tiles per compute unit: nothing to stagger, the plain tiling runs
+// The staggered form is laid out for 256 compute units (the half tiles are the first-generation
+// workgroups with bit 5 of the index set: 128 of them); on any other device, and with fewer
+// than two tiles per compute unit, the plain tiling runs.
+bool mixed_applies(int64_t tiles) { return chip().cus == 2 * MIXED_HALVES && tiles >= 2 * chip().cus; }
+
 int64_t grid_pp_mixed(int64_t M, int64_t N)
 {
     const int64_t g = grid_pp<256, 256>(M, N);
-    return g < 512 ? g : g + MIXED_HALVES;
+    return (g < 0 || !mixed_applies(g)) ? g : g + MIXED_HALVES;
 }
 
 int launch_pp_mixed(const GemmArgs& a)
 {
-    const int64_t g = grid_pp_mixed(a.M, a.N);
-    if (g < 0 || g > INT32_MAX) return GEMM_F16_ERR_SIZE;
-    if (g < 512) return launch_pp<16, 256, 256>(a);
-    TiledParams p = {};
-    p.M = (int)a.M; p.N = (int)a.N; p.K = (int)a.K;
-    p.A = a.A; p.lda = a.lda; p.B = a.B; p.ldb = a.ldb; p.C = a.C; p.ldc = a.ldc;
-    p.bias = a.bias; p.relu = a.relu;
-    p.tiles_m = (int)((a.M + 255) / 256);
-    p.tiles_n = (int)((a.N + 255) / 256);
-    p.group_m = 8 < p.tiles_m ? 8 : p.tiles_m;
+    const int64_t tiles = grid_pp<256, 256>(a.M, a.N);
+    if (tiles < 0 || tiles + MIXED_HALVES > INT32_MAX) return GEMM_F16_ERR_SIZE;
+    if (!mixed_applies(tiles)) return launch_pp<16, 256, 256>(a);
+    const int64_t g = tiles + MIXED_HALVES;
+    TiledParams p = make_tiled_params(a, 256, 256, 8);
+    p.first_generation = chip().cus;
     const bool tail = (a.K % BK) != 0;
     if (a.c_is_f16) {
         if (tail) hipLaunchKernelGGL((gemm_pp_mixed_kernel<half_t, 16, true>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
@@ -653,23 +659,18 @@ int launch_pp_mixed(const GemmArgs& a)
 int64_t grid_pp_persistent(int64_t M, int64_t N)
 {
     const int64_t g = grid_pp<256, 256>(M, N);
-    return g < compute_units() ? g : compute_units();
+    return g < chip().cus ? g : chip().cus;
 }
 
 int launch_pp_persistent(const GemmArgs& a)
 {
     const int64_t tiles = grid_pp<256, 256>(a.M, a.N);
     if (tiles < 0) return GEMM_F16_ERR_SIZE;
-    if (tiles <= compute_units()) return launch_pp<16, 256, 256>(a);      // one tile each: nothing to chain
-    const unsigned g = (unsigned)compute_units();
-    TiledParams p = {};
-    p.M = (int)a.M; p.N = (int)a.N; p.K = (int)a.K;
-    p.A = a.A; p.lda = a.lda; p.B = a.B; p.ldb = a.ldb; p.C = a.C; p.ldc = a.ldc;
-    p.bias = a.bias; p.relu = a.relu;
-    p.tiles_m = (int)((a.M + 255) / 256);
-    p.tiles_n = (int)((a.N + 255) / 256);
-    p.group_m = 8 < p.tiles_m ? 8 : p.tiles_m;
-    p.stagger_ticks = (a.K <= 2048 && tiles >= 3 * (int64_t)g) ? 1200 : 0;
+    if (tiles <= chip().cus) return launch_pp<16, 256, 256>(a);      // one tile each: nothing to chain
+    const unsigned g = (unsigned)chip().cus;
+    TiledParams p = make_tiled_params(a, 256, 256, 8);
+    p.first_generation = (int)g;
+    p.stagger_ticks = (a.K <= 2048 && tiles >= 3 * (int64_t)g) ? late_start_ticks() : 0;
     const bool tail = (a.K % BK) != 0;
     if (a.c_is_f16) {
         if (tail) hipLaunchKernelGGL((gemm_pp256_persistent_kernel<half_t, 16, true>), dim3(g), dim3(512), 0, a.stream, p);
@@ -682,31 +683,41 @@ int launch_pp_persistent(const GemmArgs& a)
 }
 
 constexpr int lds_pp(int bm, int bn) { return 2 * bm * BK * 2 + 3 * BK * bn * 2; }
-const GemmConfigDesc kPingPong = {
-    "pp256x256x64_w2x4", 256, 256, BK, 8, 128, 64, lds_pp(256, 256), true, launch_pp<32, 256, 256>, grid_pp<256, 256>};
 const GemmConfigDesc kPingPong16 = {
-    "pp256x256x64_w2x4_mi16", 256, 256, BK, 8, 128, 64, lds_pp(256, 256), true, launch_pp<16, 256, 256>, grid_pp<256, 256>};
+    "pp256x256x64_w2x4_mi16", 256, 256, BK, 8, 128, 64, lds_pp(256, 256), true, launch_pp_plain<16, 256, 256>, grid_pp<256, 256>};
 const GemmConfigDesc kPingPong16_192 = {
-    "pp192x256x64_w2x4_mi16", 192, 256, BK, 8, 96, 64, lds_pp(192, 256), true, launch_pp<16, 192, 256>, grid_pp<192, 256>};
+    "pp192x256x64_w2x4_mi16", 192, 256, BK, 8, 96, 64, lds_pp(192, 256), true, launch_pp_plain<16, 192, 256>, grid_pp<192, 256>};
 const GemmConfigDesc kPingPong16_128 = {
-    "pp128x256x64_w2x4_mi16", 128, 256, BK, 8, 64, 64, lds_pp(128, 256), true, launch_pp<16, 128, 256>, grid_pp<128, 256>};
+    "pp128x256x64_w2x4_mi16", 128, 256, BK, 8, 64, 64, lds_pp(128, 256), true, launch_pp_plain<16, 128, 256>, grid_pp<128, 256>};
 const GemmConfigDesc kPingPong16_256x192 = {
-    "pp256x192x64_w2x4_mi16", 256, 192, BK, 8, 128, 48, lds_pp(256, 192), true, launch_pp<16, 256, 192>, grid_pp<256, 192>};
+    "pp256x192x64_w2x4_mi16", 256, 192, BK, 8, 128, 48, lds_pp(256, 192), true, launch_pp_plain<16, 256, 192>, grid_pp<256, 192>};
 const GemmConfigDesc kPingPong16_128x128 = {
-    "pp128x128x64_w2x4_mi16", 128, 128, BK, 8, 64, 32, lds_pp(128, 128), true, launch_pp<16, 128, 128>, grid_pp<128, 128>};
+    "pp128x128x64_w2x4_mi16", 128, 128, BK, 8, 64, 32, lds_pp(128, 128), true, launch_pp_plain<16, 128, 128>, grid_pp<128, 128>};
 const GemmConfigDesc kPingPong16Mixed = {
     "pp256x256x64_w2x4_mi16_stag", 256, 256, BK, 8, 128, 64, lds_pp(256, 256), true, launch_pp_mixed, grid_pp_mixed};
 const GemmConfigDesc kPingPong16Persistent = {
     "pp256x256x64_w2x4_mi16_chain", 256, 256, BK, 8, 128, 64, lds_pp(256, 256), true, launch_pp_persistent, grid_pp_persistent};
+#ifdef GEMM_F16_LADDER
+// ladder rows: the same kernel on 32x32x16 MFMAs, and with the tiles dealt to the XCDs the way
+// the hardware deals workgroups (no XCD-aware order: the 8 L2s then each see tiles from all over C)
+int launch_pp_no_xcd_order(const GemmArgs& a) { return launch_pp<16, 256, 256>(a, false); }
+const GemmConfigDesc kPingPong = {
+    "pp256x256x64_w2x4", 256, 256, BK, 8, 128, 64, lds_pp(256, 256), true, launch_pp_plain<32, 256, 256>, grid_pp<256, 256>};
+const GemmConfigDesc kPingPong16NoXcd = {
+    "pp256x256x64_w2x4_mi16_noxcd", 256, 256, BK, 8, 128, 64, lds_pp(256, 256), true, launch_pp_no_xcd_order, grid_pp<256, 256>};
+#endif
 
 }  // namespace
 
 const GemmConfigDesc* pingpong16_persistent_config() { return &kPingPong16Persistent; }
 const GemmConfigDesc* pingpong16_staggered_config() { return &kPingPong16Mixed; }
-const GemmConfigDesc* pingpong_config() { return &kPingPong; }
 const GemmConfigDesc* pingpong16_config(int bm, int bn)
 {
     if (bn == 128) return &kPingPong16_128x128;
     if (bn == 192) return &kPingPong16_256x192;
     return bm == 128 ? &kPingPong16_128 : bm == 192 ? &kPingPong16_192 : &kPingPong16;
 }
+#ifdef GEMM_F16_LADDER
+const GemmConfigDesc* pingpong_config() { return &kPingPong; }
+const GemmConfigDesc* pingpong16_no_xcd_order_config() { return &kPingPong16NoXcd; }
+#endif

@@ -38,7 +38,11 @@ using namespace gemm_dev;
 // time.  Two are enough when a k step's MFMAs outlast the memory latency (large
 // tiles); a 64 x 64 tile multiplies a k step in about 60 ns and would otherwise
 // spend its time waiting for every k step in turn.
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, typename CT>
+// SWIZZLE = false (a ladder row, never selected) leaves the LDS image as the copies deliver it:
+// the fragment reads then run into bank conflicts, which is what the XOR placement is there for
+// (the paper pads its shared-memory rows instead: section "Padding to avoid bank conflicts" --
+// a direct-to-LDS copy writes lane-linearly and cannot pad).
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, typename CT, bool SWIZZLE = true>
 __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_tiled_kernel(const TiledParams p)
 {
     static_assert(STAGES >= 2 && (STAGES & (STAGES - 1)) == 0, "stage index is kt & (STAGES - 1)");
@@ -83,7 +87,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_tiled_kernel(cons
     uint32_t a_off[NTA];
     int a_chunk;                                  // logical 16-byte chunk (8 k) this lane fetches
     {
-        const int sw = 4 * (wave & 1) + (lane >> 4);              // (row/2)%8 for row = 8q + lane/8, q = wave mod 2
+        const int sw = SWIZZLE ? 4 * (wave & 1) + (lane >> 4) : 0;  // (row/2)%8 for row = 8q + lane/8, q = wave mod 2
         a_chunk = (lane & 7) ^ sw;
 #pragma unroll
         for (int t = 0; t < NTA; t++) {
@@ -102,7 +106,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_tiled_kernel(cons
 #pragma unroll
         for (int t = 0; t < NTB; t++) {
             const int krow = B_RPI * (wave + NW * t) + lane / B_LPR;
-            const int sw = (B_ROW >= 256) ? (krow & 3) : ((krow >> 1) & 1);
+            const int sw = !SWIZZLE ? 0 : (B_ROW >= 256) ? (krow & 3) : ((krow >> 1) & 1);
             const int chunk = pos ^ (sw << 2);
             int col = 8 * chunk;
             col = (n0 + col + 8 <= p.N) ? col : 0;                  // clamp: loaded, never stored
@@ -157,7 +161,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_tiled_kernel(cons
     uint32_t a_rd[BK / 16];
     {
         const uint32_t row_off = (uint32_t)(wm_base + (lane & 31)) * (BK * 2);
-        const int sw = (lane >> 1) & 7;
+        const int sw = SWIZZLE ? (lane >> 1) & 7 : 0;
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ks++)
             a_rd[ks] = smem_base + row_off + (uint32_t)(((2 * ks + (lane >> 5)) ^ sw) * 16);
@@ -171,7 +175,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_tiled_kernel(cons
     {
         const int blk = lane >> 4, j = lane & 15;
         const uint32_t lane_off = (uint32_t)(8 * (blk >> 1) + (j >> 2)) * B_ROW + (uint32_t)(16 * (blk & 1) + 4 * (j & 3)) * 2;
-        const int sw = (B_ROW >= 256) ? (j >> 2) : ((j >> 3) & 1);   // swizzle term of this lane's k row
+        const int sw = !SWIZZLE ? 0 : (B_ROW >= 256) ? (j >> 2) : ((j >> 3) & 1);   // swizzle term of this lane's k row
 #pragma unroll
         for (int fn = 0; fn < FN; fn++)
             b_rd[fn] = smem_base + A_STAGE + lane_off + (uint32_t)((((wn_base >> 5) + fn) ^ sw) * 64);
@@ -277,42 +281,45 @@ int64_t grid_tiled(int64_t M, int64_t N)
     return tm * tn;
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, bool SWIZZLE = true>
 int launch_tiled(const GemmArgs& a)
 {
     const int64_t g = grid_tiled<BM, BN, WAVES_M, WAVES_N>(a.M, a.N);
     if (g < 0) return GEMM_F16_ERR_SIZE;
-    TiledParams p = {};
-    p.M = (int)a.M; p.N = (int)a.N; p.K = (int)a.K;
-    p.A = a.A; p.lda = a.lda; p.B = a.B; p.ldb = a.ldb; p.C = a.C; p.ldc = a.ldc;
-    p.bias = a.bias; p.relu = a.relu;
-    p.tiles_m = (int)((a.M + BM - 1) / BM);
-    p.tiles_n = (int)((a.N + BN - 1) / BN);
     // 32 workgroups of an XCD that run together should form a near-square block of C
-    p.group_m = (BM >= 256) ? 8 : 16;
-    if (p.group_m > p.tiles_m) p.group_m = p.tiles_m;
+    const TiledParams p = make_tiled_params(a, BM, BN, (BM >= 256) ? 8 : 16);
     constexpr int threads = WAVES_M * WAVES_N * 64;
     if (a.c_is_f16)
-        hipLaunchKernelGGL((gemm_tiled_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, half_t>), dim3((unsigned)g), dim3(threads), 0, a.stream, p);
+        hipLaunchKernelGGL((gemm_tiled_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, half_t, SWIZZLE>), dim3((unsigned)g), dim3(threads), 0, a.stream, p);
     else
-        hipLaunchKernelGGL((gemm_tiled_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, float>), dim3((unsigned)g), dim3(threads), 0, a.stream, p);
+        hipLaunchKernelGGL((gemm_tiled_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, float, SWIZZLE>), dim3((unsigned)g), dim3(threads), 0, a.stream, p);
     return hipGetLastError() == hipSuccess ? GEMM_F16_OK : GEMM_F16_ERR_LAUNCH;
 }
 
-#ifndef T64_STAGES
-#define T64_STAGES 4
-#endif
-#define TILED_CONFIG(NAME, BM, BN, WMS, WNS, ST)                                                    \
+#define TILED_CONFIG(NAME, BM, BN, WMS, WNS, ST, SWZ)                                               \
     { NAME, BM, BN, BK, (WMS) * (WNS), (BM) / (WMS), (BN) / (WNS), (ST) * ((BM) + (BN)) * BK * 2,   \
-      true, launch_tiled<BM, BN, WMS, WNS, ST>, grid_tiled<BM, BN, WMS, WNS> }
+      true, launch_tiled<BM, BN, WMS, WNS, ST, SWZ>, grid_tiled<BM, BN, WMS, WNS> }
 
-const GemmConfigDesc kTiled[] = {
-    TILED_CONFIG("t256x256x64_w2x4", 256, 256, 2, 4, 2),
-    TILED_CONFIG("t128x128x64_w2x2", 128, 128, 2, 2, 2),
-    TILED_CONFIG("t64x64x64_w2x2", 64, 64, 2, 2, T64_STAGES),
-};
+const GemmConfigDesc kTiled64 = TILED_CONFIG("t64x64x64_w2x2", 64, 64, 2, 2, 4, true);
+#ifdef GEMM_F16_LADDER
+const GemmConfigDesc kTiled128 = TILED_CONFIG("t128x128x64_w2x2", 128, 128, 2, 2, 2, true);
+const GemmConfigDesc kTiled256 = TILED_CONFIG("t256x256x64_w2x4", 256, 256, 2, 4, 2, true);
+const GemmConfigDesc kTiled256NoSwizzle = TILED_CONFIG("t256x256x64_w2x4_noswz", 256, 256, 2, 4, 2, false);
+#endif
 
 }  // namespace
 
-int tiled_num_configs() { return (int)(sizeof(kTiled) / sizeof(kTiled[0])); }
-const GemmConfigDesc* tiled_config(int i) { return &kTiled[i]; }
+// block = 64: the smallest problems.  Ladder builds: 128 and 256, the same kernel at the
+// larger tiles (comparison rows; the phase-alternating kernel serves those sizes).
+const GemmConfigDesc* tiled_config(int block)
+{
+#ifdef GEMM_F16_LADDER
+    if (block == 128) return &kTiled128;
+    if (block == 256) return &kTiled256;
+#endif
+    (void)block;
+    return &kTiled64;
+}
+#ifdef GEMM_F16_LADDER
+const GemmConfigDesc* tiled_no_swizzle_config() { return &kTiled256NoSwizzle; }
+#endif

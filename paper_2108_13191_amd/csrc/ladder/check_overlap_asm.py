@@ -1,4 +1,4 @@
-"""Build-time check of csrc/gemm_overlap.hip's generated code.
+"""Build-time check of the generated code of gemm_overlap.hip (beside this file).
 
 That kernel requests slabs of C with inline-assembly loads whose results are
 used two k steps later, after a wait that the pipeline implies; the compiler is
@@ -8,7 +8,7 @@ kernel emits where the slab is known to have arrived ("; C slab arrived
 <registers>").  `hazards()` scans the assembly hipcc produces for exactly that;
 tests/test_abi_host.py runs it on every build of the test suite.
 
-    python -m paper_2108_13191_amd.check_overlap_asm        # compiles to assembly and checks
+    python paper_2108_13191_amd/csrc/ladder/check_overlap_asm.py        # compiles to assembly and checks
 """
 from __future__ import annotations
 
@@ -19,7 +19,7 @@ import sys
 import tempfile
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SOURCE = os.path.join(HERE, "csrc", "gemm_overlap.hip")
+SOURCE = os.path.join(HERE, "gemm_overlap.hip")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-S", "--cuda-device-only"]
 

@@ -46,8 +46,8 @@
 //
 // Requirements: as for the other tuned kernels, and K a multiple of 64 with at
 // least 9 k steps (other problems are passed on to the 256 x 256 kernel).
-#include "gemm_device.h"
-#include "../../include/gemm_f16.h"
+#include "../gemm_device.h"
+#include "../../../include/gemm_f16.h"
 
 namespace {
 
@@ -402,7 +402,7 @@ int64_t grid_overlap(int64_t M, int64_t N)
     const int64_t tm = (M + OBM - 1) / OBM, tn = (N + OBN - 1) / OBN;
     if (tm > 0 && tn > INT32_MAX / tm) return -1;
     const int64_t g = tm * tn;
-    return g < compute_units() ? g : compute_units();
+    return g < chip().cus ? g : chip().cus;
 }
 
 int launch_overlap(const GemmArgs& a)
@@ -411,13 +411,7 @@ int launch_overlap(const GemmArgs& a)
     if (g < 0) return GEMM_F16_ERR_SIZE;
     // k tails and very short k loops: the plain 256 x 256 launch (the selector never sends such problems here)
     if (a.K % BK != 0 || a.K / BK < MIN_KT) return pingpong16_config(256, 256)->launch(a);
-    TiledParams p = {};
-    p.M = (int)a.M; p.N = (int)a.N; p.K = (int)a.K;
-    p.A = a.A; p.lda = a.lda; p.B = a.B; p.ldb = a.ldb; p.C = a.C; p.ldc = a.ldc;
-    p.bias = a.bias; p.relu = a.relu;
-    p.tiles_m = (int)((a.M + OBM - 1) / OBM);
-    p.tiles_n = (int)((a.N + OBN - 1) / OBN);
-    p.group_m = 8 < p.tiles_m ? 8 : p.tiles_m;
+    TiledParams p = make_tiled_params(a, OBM, OBN, 8);
     if (a.c_is_f16) hipLaunchKernelGGL((gemm_pp_overlap_kernel<half_t>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
     else            hipLaunchKernelGGL((gemm_pp_overlap_kernel<float>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
     return hipGetLastError() == hipSuccess ? GEMM_F16_OK : GEMM_F16_ERR_LAUNCH;

@@ -45,8 +45,8 @@
 // Requirements as for the other tuned kernels: A, B 16-byte aligned; lda, ldb,
 // K, N multiples of 8.  Rows >= M / columns >= N are fetched from clamped
 // addresses and never stored; the k tail is zero-filled through registers.
-#include "gemm_device.h"
-#include "../../include/gemm_f16.h"
+#include "../gemm_device.h"
+#include "../../../include/gemm_f16.h"
 
 namespace {
 
@@ -319,13 +319,8 @@ int launch_w4(const GemmArgs& a)
     const int64_t g = grid_w4(a.M, a.N);
     if (g < 0) return GEMM_F16_ERR_SIZE;
     if (a.bias || a.relu) return GEMM_F16_ERR_CONFIG;      // this comparison kernel has no fused epilogue
-    TiledParams p = {};
+    TiledParams p = make_tiled_params(a, WBM, WBN, 8);     // an XCD's 32 concurrent tiles form an 8 x 4 block of C
     p.bias = nullptr; p.relu = 0;
-    p.M = (int)a.M; p.N = (int)a.N; p.K = (int)a.K;
-    p.A = a.A; p.lda = a.lda; p.B = a.B; p.ldb = a.ldb; p.C = a.C; p.ldc = a.ldc;
-    p.tiles_m = (int)((a.M + WBM - 1) / WBM);
-    p.tiles_n = (int)((a.N + WBN - 1) / WBN);
-    p.group_m = 8 < p.tiles_m ? 8 : p.tiles_m;     // an XCD's 32 concurrent tiles form an 8 x 4 block of C
     if (a.c_is_f16)
         hipLaunchKernelGGL(gemm_w4_kernel<half_t>, dim3((unsigned)g), dim3(256), 0, a.stream, p);
     else

@@ -10,19 +10,30 @@ CANARY16 = np.float16(-1234.0)
 CANARY32 = np.float32(-1234.0)
 
 
+def config_id(name: str) -> int:
+    """Index of the configuration with this name in the active library's table."""
+    for i in range(binding.num_configs()):
+        if binding.describe_config(i)["name"] == name:
+            return i
+    raise KeyError(name)
+
+
 class DevMat:
     """A rows x cols matrix inside a larger device buffer: row pitch `ld`
     elements, first element `offset` elements into the allocation; everything
-    around the matrix holds a canary value."""
+    around the matrix holds a canary value: NaN for an operand that is only read (a
+    kernel that multiplies padding, even by zero, shows it in the result), a finite
+    value for C, where "everything outside the matrix is untouched" is checked by
+    comparing bits."""
 
-    def __init__(self, host: np.ndarray, ld=None, offset=0):
+    def __init__(self, host: np.ndarray, ld=None, offset=0, nan_canary=False):
         rows, cols = host.shape
         self.rows, self.cols = rows, cols
         self.ld = cols if ld is None else ld
         assert self.ld >= cols
         self.offset = offset
         n = offset + max(rows, 1) * max(self.ld, 1) + 8
-        canary = CANARY16 if host.dtype == np.float16 else CANARY32
+        canary = host.dtype.type(np.nan) if nan_canary else CANARY16 if host.dtype == np.float16 else CANARY32
         buf = np.full(n, canary, dtype=host.dtype)
         view = buf[offset:offset + rows * self.ld].reshape(rows, self.ld) if rows and self.ld else buf[:0].reshape(rows, 0)
         if rows and cols:
@@ -42,7 +53,7 @@ class DevMat:
         mask = np.ones(buf.shape, dtype=bool)
         inner = mask[self.offset:self.offset + self.rows * self.ld].reshape(self.rows, self.ld)
         inner[:, :self.cols] = False
-        assert np.array_equal(buf[mask], self.host_buf[mask]), "memory outside C was written"
+        assert np.array_equal(buf[mask].view(np.uint8), self.host_buf[mask].view(np.uint8)), "memory outside C was written"
         return out
 
 
@@ -50,7 +61,7 @@ def run_gemm(A, B, C0, mode, lda=None, ldb=None, ldc=None, offs=(0, 0, 0), expec
     """Run the library on device copies of A, B, C0; return the new C (numpy)."""
     M, K = A.shape
     N = B.shape[1]
-    dA, dB, dC = DevMat(A, lda, offs[0]), DevMat(B, ldb, offs[1]), DevMat(C0, ldc, offs[2])
+    dA, dB, dC = DevMat(A, lda, offs[0], nan_canary=True), DevMat(B, ldb, offs[1], nan_canary=True), DevMat(C0, ldc, offs[2])
     fn = binding.gemm_f16_f32acc if mode == "f32" else binding.gemm_f16_f16acc
     rc = fn(M, N, K, dA.ptr, dA.ld, dB.ptr, dB.ld, dC.ptr, dC.ld, torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()

@@ -114,7 +114,7 @@ def test_chained_and_late_started_launch_under_hip_graph_capture(oracle_mod):
     q = binding.query_config(0, M, N, K, 256, K, 256, N, 256, N)
     assert q["name"].endswith("_chain") and q["grid"] == 256, q
     A, B, C0 = wl.make_inputs(M, N, K, "int2", "zeros", seed=51)
-    dA, dB, dC = DevMat(A), DevMat(B), DevMat(C0)
+    dA, dB, dC = DevMat(A, nan_canary=True), DevMat(B, nan_canary=True), DevMat(C0)
     Cref, _ = oracle_mod.gemm_f16(A, B, C0)
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())

@@ -27,10 +27,12 @@ def _id(name=NAME):
 
 
 @pytest.fixture(autouse=True)
-def _auto_config():
-    binding.force_config(-1)
-    yield
-    binding.force_config(-1)
+def _ladder_library():
+    # the kernel is a comparison row: it lives in the ladder build of the library
+    with binding.library("ladder"):
+        binding.force_config(-1)
+        yield
+        binding.force_config(-1)
 
 
 # tiles of 256 x 128: 1, 15, 260 (two for 4 workgroups), 512, 1080, 1320

@@ -15,7 +15,7 @@ if not torch.cuda.is_available():
     pytest.skip("no GPU", allow_module_level=True)
 
 from paper_2108_13191_amd import binding, workloads as wl   # noqa: E402
-from gpu_util import run_gemm, assert_close                  # noqa: E402
+from gpu_util import run_gemm, assert_close, config_id, TOL   # noqa: E402
 
 CDT = {"f32": np.float32, "f16": np.float16}
 ALL_CONFIGS = list(range(binding.num_configs()))
@@ -205,7 +205,7 @@ def test_two_streams_concurrently(oracle_mod):
     cases = []
     for seed, (M, N, K) in enumerate([(1536, 1280, 2048), (1100, 2056, 1544)]):
         A, B, C0 = wl.make_inputs(M, N, K, "int2", "zeros", seed=40 + seed)
-        cases.append((A, B, C0, DevMat(A), DevMat(B), DevMat(C0), torch.cuda.Stream()))
+        cases.append((A, B, C0, DevMat(A, nan_canary=True), DevMat(B, nan_canary=True), DevMat(C0), torch.cuda.Stream()))
     torch.cuda.synchronize()
     for _ in range(3):
         for A, B, C0, dA, dB, dC, s in cases:
@@ -224,7 +224,7 @@ def test_under_hip_graph_capture(oracle_mod):
     from gpu_util import DevMat
     M, N, K = 1024, 1032, 520
     A, B, C0 = wl.make_inputs(M, N, K, "int2", "zeros", seed=50)
-    dA, dB, dC = DevMat(A), DevMat(B), DevMat(C0)
+    dA, dB, dC = DevMat(A, nan_canary=True), DevMat(B, nan_canary=True), DevMat(C0)
     Cref, _ = oracle_mod.gemm_f16(A, B, C0)
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
@@ -260,3 +260,64 @@ def test_row_split_plan(oracle_mod, mode):
     _check(oracle_mod, A, B, C0, mode, exact=True, what=f"row split {q}")
     A, B, C0 = wl.make_inputs(M, N, K, "uniform", "uniform", seed=62, c_dtype=CDT[mode])
     _check(oracle_mod, A, B, C0, mode, what=f"row split {q}")
+
+
+# ---- NaN and infinities through the plain entry points -------------------------
+
+def _class_of(x):
+    """0 finite, 1 +inf, 2 -inf, 3 NaN."""
+    x = np.asarray(x, dtype=np.float64)
+    return np.where(np.isnan(x), 3, np.where(np.isposinf(x), 1, np.where(np.isneginf(x), 2, 0)))
+
+
+@pytest.mark.parametrize("mode", ["f32", "f16"])
+@pytest.mark.parametrize("name", ["pp256x256x64_w2x4_mi16", "pp128x128x64_w2x4_mi16", "t64x64x64_w2x2", "generic64x64x32"])
+def test_nan_and_inf_propagate_like_ieee(oracle_mod, name, mode):
+    """NaN and +-inf inside A, B and C0 reach exactly the outputs the definition says (the
+    oracle's binary64 sum gives the class of every element: NaN where a NaN or inf - inf or
+    0 * inf enters the sum, an infinity where only one sign of infinity does); all other
+    outputs meet the tolerance.  A k tail (K = 200) and ragged edges: zero-filled padding
+    must not meet a NaN or an infinity."""
+    binding.force_config(config_id(name))
+    M, N, K = 300, 264, 200
+    A, B, C0 = wl.make_inputs(M, N, K, "uniform", "uniform", seed=31, c_dtype=CDT[mode])
+    A[5, 17] = np.nan                    # a NaN row of results
+    A[40, 199] = np.inf                  # in the k tail's last element: +-inf by the sign of B[199, j]
+    B[0, 7] = -np.inf                    # a column: -inf * A[i, 0]
+    A[41, 3] = np.inf
+    B[3, 9] = 0.0                        # inf * 0 = NaN at (41, 9)
+    C0[77, 100] = np.inf
+    C0[78, 101] = np.nan
+    A[299, 0] = np.inf                   # last row (edge tile) times the -inf column: (299, 7) = inf * -inf = -inf
+    got = run_gemm(A, B, C0, mode)
+    with np.errstate(invalid="ignore", over="ignore"):
+        Cref, S = oracle_mod.gemm_f16(A, B, C0)
+    want_cls, got_cls = _class_of(Cref), _class_of(got)
+    if mode == "f16":                    # finite sums beyond the f16 range become infinities on the store
+        with np.errstate(over="ignore", invalid="ignore"):
+            want_cls = _class_of(Cref.astype(np.float16))
+    assert np.array_equal(got_cls, want_cls), np.argwhere(got_cls != want_cls)[:5]
+    assert want_cls[5].min() == 3 and want_cls[41, 9] == 3 and want_cls[299, 7] == 2 and want_cls[77, 100] == 1
+    fin = want_cls == 0
+    with np.errstate(invalid="ignore"):
+        err = np.abs(got.astype(np.float64) - Cref)[fin]
+    bound = (TOL[mode] * (S + np.abs(C0.astype(np.float64))))[fin]
+    assert np.all(err <= bound)
+
+
+# ---- the late start of every other XCD on the one-workgroup-per-tile launches --------
+
+@pytest.mark.parametrize("mode", ["f32", "f16"])
+@pytest.mark.parametrize("case", [("pp256x256x64_w2x4_mi16", (8448, 8192, 128)),      # 1056 tiles, K a multiple of 64
+                                  ("pp256x256x64_w2x4_mi16", (8300, 8200, 200)),      # 1089 tiles, ragged, k tail
+                                  ("pp128x128x64_w2x4_mi16", (5900, 5640, 72))])      # 2115 tiles (two per compute unit at once)
+def test_late_started_plain_launches(oracle_mod, case, mode):
+    """Four or more rounds of workgroups and K <= 2048: the workgroups that begin with the
+    launch on every other XCD wait about 12 us first.  Results must not depend on it."""
+    name, (M, N, K) = case
+    binding.force_config(config_id(name))
+    A, B, C0 = wl.make_inputs(M, N, K, "int2", "int2", seed=K, c_dtype=CDT[mode])
+    got = run_gemm(A, B, C0, mode)
+    Cref, _ = oracle_mod.gemm_f16(A, B, C0)
+    want = oracle_mod.round_to_f32(Cref) if mode == "f32" else oracle_mod.round_to_f16(Cref)
+    assert np.array_equal(got, want), f"{name} {(M, N, K)} {mode}"
