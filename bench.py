@@ -8,8 +8,20 @@ store.  Inputs are resident in HBM before the timed region.  Prints ONE JSON
 line: TFLOP/s = 2 M N K / time, the roofline of the kernel measured with HIP
 events on the launch stream, and the CPU oracle timed on a bounded row sample.
 
+Order of the legs of a default run, all on one stream and without a pause between
+the first three: (1) an MFMA-only loop on operands drawn from the workload's own
+distribution, about 45 ms -- the throughput the matrix units sustain on that data
+before a single byte moves (`mfma_only_ceiling`); (2) the headline: W untimed and
+exactly K timed f32-accumulate calls (`value`); (3) the same for the
+f16-accumulate mode (`f16acc`); (4) the CPU oracle; (5) the headline protocol once
+more right after the GPU has sat idle under (4) (`after_idle`): the part's power
+management answers a load step with a transient of about 25 launches (two fast
+ones, five about 30 % slow, a slow recovery), which is all a 5 + 20 launch run
+sees when it starts cold.  `value` is the steady state; `after_idle` and the
+quarter means of the timed series (`series`) show the transient and any drift.
+
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
-                    [--mode f32|f16] [--no-cpu] [--sweep]
+                    [--mode f32|f16] [--no-cpu] [--sweep] [--cold]
 """
 from __future__ import annotations
 
@@ -49,26 +61,86 @@ def kernel_symbol(tile_name, mode, K=0):
         return f"gemm_pp_overlap_kernel<{ct}>"
     if tile_name.startswith("w4_"):
         return f"gemm_w4_kernel<{ct}>"
+    if tile_name.startswith("il"):
+        return f"gemm_il256_kernel<{ct}>"
     if tile_name.startswith("generic"):
-        return f"gemm_generic_kernel<{ct}>"
+        return f"gemm_generic_kernel<{ct}, {'true' if tile_name.endswith('_c_in_loop') else 'false'}>"
     # t<BM>x<BN>x64_w<WM>x<WN>: template arguments BM, BN, waves along m, along n, LDS stages, C type
     import re
     bm, bn, wm, wn = (int(x) for x in re.match(r"t(\d+)x(\d+)x\d+_w(\d+)x(\d+)", tile_name).groups())
-    return f"gemm_tiled_kernel<{bm}, {bn}, {wm}, {wn}, {4 if bm == 64 else 2}, {ct}>"
+    return f"gemm_tiled_kernel<{bm}, {bn}, {wm}, {wn}, {4 if bm == 64 else 2}, {ct}, {'false' if tile_name.endswith('_noswz') else 'true'}>"
 
 
 def measured_traffic(tile_name, workload, mode):
     """HBM bytes per launch (FETCH_SIZE + WRITE_SIZE from rocprofv3 --pmc runs,
     scaled by a copy kernel of known size) if a committed profile summary under
-    profiles/ records them for this kernel and workload; otherwise None."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{tile_name}_{workload}_{mode}.md")
+    profiles/ records them for this kernel and workload, and where the figure comes
+    from; (None, reason) otherwise.  Counters cannot be read from inside this
+    program: the figure is the committed one, not one of this run."""
+    rel = os.path.join("profiles", f"hbm_traffic_{tile_name}_{workload}_{mode}.md")
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, rel)):
             if line.startswith("traffic_bytes_per_launch:"):
-                return int(float(line.split(":", 1)[1].strip()))
+                return int(float(line.split(":", 1)[1].strip())), f"{rel} (rocprofv3 --pmc runs of this command, committed; not measured in this run)"
     except OSError:
         pass
-    return None
+    return None, "no committed counter run for this kernel and workload"
+
+
+PROBE_LIB = os.path.join(ROOT, "libbench_probe.so")
+
+
+def build_probe():
+    """Compile bench_probe.hip (the MFMA-only loop) next to this file."""
+    import subprocess
+    subprocess.run(["hipcc", "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
+                    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
+                    "-o", PROBE_LIB, os.path.join(ROOT, "bench_probe.hip")], check=True, capture_output=True)
+    return PROBE_LIB
+
+
+def mfma_only_ceiling(torch, np, wl, dist, K, seconds=0.045):
+    """TFLOP/s of a loop of nothing but v_mfma_f32_16x16x32_f16 (two wavefronts per SIMD, the
+    library's register blocking, operands in registers) on f16 operands drawn from `dist`,
+    the workload's distribution: the data-dependent, power-limited ceiling of the matrix
+    units.  Runs about `seconds` in three launches; the figure is the last launch's."""
+    import ctypes
+    if not os.path.exists(PROBE_LIB):
+        build_probe()
+    lib = ctypes.CDLL(PROBE_LIB)
+    lib.bench_mfma_only.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    lib.bench_mfma_only.restype = ctypes.c_int
+    rng = np.random.default_rng(0)
+    frags = torch.from_numpy(wl._draw(rng, (12 * 256, 8), dist, K).astype(np.float16)).cuda()
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    stream = torch.cuda.current_stream()
+
+    def run(iters):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        rc = lib.bench_mfma_only(frags.data_ptr(), sink.data_ptr(), iters, cus, stream.cuda_stream)
+        e1.record(stream)
+        if rc != 0:
+            raise RuntimeError(f"bench_mfma_only returned {rc}")
+        return e0, e1, iters
+
+    e0, e1, it = run(2000)
+    torch.cuda.synchronize()
+    per_iter_ms = max(e0.elapsed_time(e1) / it, 1e-7)
+    iters = int(max(1000, seconds / 3 * 1e3 / per_iter_ms))
+    launches = [run(iters) for _ in range(3)]          # queued back to back; the caller's next leg follows without a pause
+    return launches, cus
+
+
+def ceiling_result(launches, cus):
+    e0, e1, iters = launches[-1]
+    ms = e0.elapsed_time(e1)
+    flops = float(cus) * 8 * iters * 32 * 16384
+    return {"value": round(flops / (ms * 1e-3) / 1e12, 1), "unit": "TFLOP/s", "ms": round(ms, 3),
+            "frac_of_peak": round(flops / (ms * 1e-3) / 1e12 / PEAK_F16_MFMA_TFLOPS, 4),
+            "what": "v_mfma_f32_16x16x32_f16 only, two wavefronts per SIMD, 8 x 4 accumulator blocks per wavefront, "
+                    "operands in registers drawn from the workload's distribution; last of three back-to-back launches"}
 
 
 def time_gemm(binding, torch, mode, M, N, K, sets, steps, warmup):
@@ -111,8 +183,10 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=40,
-                    help="untimed launches first; the shader clock needs about 25 ms of work to settle after a pause")
+    ap.add_argument("--warmup", type=int, default=10, help="untimed launches in front of the timed ones")
+    ap.add_argument("--cold", action="store_true",
+                    help="leave out the MFMA-only leg in front of the timed region (the timed launches then "
+                         "start on an idle GPU and show the transient of its power management)")
     ap.add_argument("--workload", default="sq8192_normal")
     ap.add_argument("--mode", default="f32", choices=["f32", "f16"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
@@ -122,6 +196,7 @@ def main():
                          "(calibration of the FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
     ap.add_argument("--sweep", action="store_true", help="also time every workload and the square sweep (extra lines on stderr)")
     ap.add_argument("--force-config", type=int, default=-1)
+    ap.add_argument("--ladder", action="store_true", help="use libgemm_f16_ladder.so (for --force-config on a comparison kernel)")
     ap.add_argument("--rotate", default="auto", choices=["auto", "on", "off"],
                     help="launch i works on operand set i mod R (R sets, 1 GiB or more in total), so that no launch finds "
                          "its operands in the last-level cache; auto: for problems under 512 MiB, and the same-set "
@@ -146,23 +221,35 @@ def main():
         print(json.dumps({"copy_probe_bytes_read_per_copy": n, "copy_probe_bytes_written_per_copy": n,
                           "copies": args.warmup + args.steps}))
         return
+    if args.ladder:
+        binding._active = "ladder"          # the library that also holds the comparison kernels (same selection)
     binding.load()
     binding.force_config(args.force_config)
     dev = torch.device("cuda:0")
 
-    def run_workload(name, mode, steps, warmup, shape=None, rotate=False):
+    def prepare(name, mode, shape=None, rotate=False, host=None):
+        """Operands of a workload on the device (R rotating sets if `rotate`); `host` reuses
+        the A and B another mode's call has drawn."""
         if shape is None:
             M, N, K, dab, dc, _ = wl.WORKLOADS[name]
         else:
             M, N, K, dab, dc = (*shape, "uniform", "zeros")
         cdt = np.float32 if mode == "f32" else np.float16
-        A, B, C0 = wl.make_inputs(M, N, K, dab, dc, seed=0, c_dtype=cdt)
+        if host is None:
+            A, B, C0 = wl.make_inputs(M, N, K, dab, dc, seed=0, c_dtype=cdt)
+        else:
+            A, B, C0 = host[0], host[1], host[2].astype(cdt)
         dA, dB, dC = (torch.from_numpy(x).to(dev) for x in (A, B, C0))
         sets = [(dA, dB, dC)]
         if rotate:
             for _ in range(rotation_sets(algorithmic_bytes(M, N, K, 4 if mode == "f32" else 2)) - 1):
                 sets.append((dA.clone(), dB.clone(), dC.clone()))
+        return dict(M=M, N=N, K=K, mode=mode, sets=sets, host=(A, B, C0), dist=dab)
+
+    def timed(prep, steps, warmup):
+        M, N, K, mode, sets = prep["M"], prep["N"], prep["K"], prep["mode"], prep["sets"]
         ms, per, wall = time_gemm(binding, torch, mode, M, N, K, sets, steps, warmup)
+        dA, dB, dC = sets[0]
         cfg = binding.query_config(mode == "f16", M, N, K, dA, dA.stride(0), dB, dB.stride(0), dC, dC.stride(0))
         flops = 2.0 * M * N * K
         if cfg.get("split_rows"):
@@ -170,7 +257,13 @@ def main():
         else:
             cfg["plan"] = cfg["name"]
         return dict(M=M, N=N, K=K, ms=ms, per=per, wall_ms=wall, tflops=flops / (ms * 1e-3) / 1e12, cfg=cfg, sets=len(sets),
-                    bytes=algorithmic_bytes(M, N, K, 4 if mode == "f32" else 2)), (A, B, C0)
+                    bytes=algorithmic_bytes(M, N, K, 4 if mode == "f32" else 2))
+
+    def quarters(per):
+        """Mean launch time of the first and of the last quarter of the timed series (as launched)."""
+        q = max(1, len(per) // 4)
+        return {"first_quarter_ms": round(sum(per[:q]) / q, 5), "last_quarter_ms": round(sum(per[-q:]) / q, 5),
+                "median_ms": round(sorted(per)[len(per) // 2], 5), "min_ms": round(min(per), 5)}
 
     # A problem whose operands fit the 256 MB last-level cache a few times over is
     # timed on rotating operand sets (every launch reads from HBM); the figure with
@@ -179,9 +272,18 @@ def main():
         return algorithmic_bytes(m, n, k, 4 if mode == "f32" else 2) < ROTATE_BELOW_BYTES
 
     m0, n0, k0 = wl.WORKLOADS[args.workload][:3]
+    modes = wl.WORKLOADS[args.workload][5]
+    other = {"f32": "f16", "f16": "f32"}[args.mode]
     rot = small(m0, n0, k0, args.mode) if args.rotate == "auto" else args.rotate == "on"
-    r, (A, B, C0) = run_workload(args.workload, args.mode, args.steps, args.warmup, rotate=rot)
-    same_set = run_workload(args.workload, args.mode, args.steps, args.warmup)[0] if rot and args.rotate == "auto" else None
+    # everything on the device before the first timed leg, so that the legs follow each other without a pause
+    prep = prepare(args.workload, args.mode, rotate=rot)
+    prep_other = prepare(args.workload, other, rotate=rot, host=prep["host"]) if other in modes else None
+    prep_same = prepare(args.workload, args.mode, host=prep["host"]) if rot and args.rotate == "auto" else None
+    A, B, C0 = prep["host"]
+    launches = None if args.cold else mfma_only_ceiling(torch, np, wl, prep["dist"], k0)
+    r = timed(prep, args.steps, args.warmup)
+    r_other = timed(prep_other, args.steps, args.warmup) if prep_other else None
+    same_set = timed(prep_same, args.steps, args.warmup) if prep_same else None
     M, N, K = r["M"], r["N"], r["K"]
     per = sorted(r["per"])
     avg_launch_ms = sum(per) / len(per)
@@ -195,7 +297,7 @@ def main():
         gbs = r["bytes"] / (avg_launch_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None}
-    roofline["traffic"] = measured_traffic(r["cfg"]["name"], args.workload, args.mode)
+    roofline["traffic"], roofline["traffic_source"] = measured_traffic(r["cfg"]["name"], args.workload, args.mode)
     kernels = kernel_symbol(r["cfg"]["name"], args.mode, K)
     if r["cfg"].get("split_rows"):          # two launches: the time below is that of the pair
         kernels += " + " + kernel_symbol(binding.describe_config(r["cfg"]["id2"])["name"], args.mode, K)
@@ -215,6 +317,10 @@ def main():
                "kind": "oracle", "seconds": round(dt, 2),
                "sample": f"first {nrows} of {M} rows of C (all {N} columns, full K={K}) of the same workload, "
                          f"binary64 triple loop incl. decoding B; host has {os.cpu_count()} logical CPUs"}
+    # the same protocol once more after the GPU has been idle (under the CPU leg, or for a second)
+    if args.no_cpu:
+        time.sleep(1.0)
+    idle = timed(prep, args.steps, args.warmup)
 
     out = {
         "metric": "TFLOP/s (2MNK/time), f16 GEMM " + ("f32" if args.mode == "f32" else "f16") + "-accumulate, M=N=K=8192"
@@ -225,9 +331,23 @@ def main():
         "data": "synthetic", "pct_of_f16_mfma_peak": round(100 * r["tflops"] / PEAK_F16_MFMA_TFLOPS, 2),
         "config": {"workload": f"{args.workload}: M={M} N={N} K={K}, mode {args.mode}", "tile": r["cfg"]["plan"],
                    "grid": r["cfg"]["grid"], "host_wall_ms_per_step": round(r["wall_ms"], 5),
-                   "operand_sets": r["sets"]},
+                   "operand_sets": r["sets"],
+                   "timed_region": ("starts cold (--cold)" if args.cold else
+                                    "follows the MFMA-only leg and the warm-up launches without a pause (steady state)")},
         "roofline": roofline, "cpu_baseline": cpu,
+        "series": quarters(r["per"]),
+        "after_idle": {"value": round(idle["tflops"], 2), "ms_per_step": round(idle["ms"], 5), **quarters(idle["per"]),
+                       "what": "the same W + K launches started right after the GPU sat idle (under the CPU leg): "
+                               "the transient of the part's power management, not the kernel"},
     }
+    if launches is not None:
+        ceil = ceiling_result(*launches)
+        ceil["value_over_ceiling"] = round(r["tflops"] / ceil["value"], 4)
+        out["mfma_only_ceiling"] = ceil
+    if r_other is not None:
+        out[other + "acc"] = {"value": round(r_other["tflops"], 2), "ms_per_step": round(r_other["ms"], 5),
+                              "frac": round(r_other["tflops"] / PEAK_F16_MFMA_TFLOPS, 4), "tile": r_other["cfg"]["plan"],
+                              **quarters(r_other["per"])}
 
     if same_set is not None:
         out["same_operands_every_launch"] = {"value": round(same_set["tflops"], 2), "ms_per_step": round(same_set["ms"], 5)}
@@ -237,10 +357,9 @@ def main():
         # untimed launches first (the first launches after a pause run at a lower
         # clock), then about 40 ms of timed ones
         def warm_run(name, mode, shape=None, rotate=False):
-            probe, _ = run_workload(name, mode, 3, 2, shape)
-            est = max(probe["ms"], 1e-3)
-            return run_workload(name, mode, int(min(400, max(10, 40.0 / est))), int(min(400, max(3, 25.0 / est))), shape,
-                                rotate=rotate)[0]
+            pr = prepare(name, mode, shape, rotate)
+            est = max(timed(pr, 3, 2)["ms"], 1e-3)
+            return timed(pr, int(min(400, max(10, 40.0 / est))), int(min(400, max(3, 25.0 / est))))
 
         extra = []
 
