@@ -64,6 +64,19 @@ __device__ __forceinline__ void async_copy16(const void* base, uint32_t byte_off
                  :: "v"(byte_off), "s"(base), "s"(lds_byte_addr) : "memory", "m0");
 }
 
+// The same copy in two instructions that the caller separates by at least one other instruction
+// (the wait state between a write of M0 and an LDS-DMA load): set_m0 puts base + imm into M0
+// (imm must fold to a compile-time constant), async_copy16_m0 is the load.  Nothing in between
+// may write M0; the kernels that use the pair issue nothing but MFMAs there.
+__device__ __forceinline__ void set_m0(uint32_t base, uint32_t imm)
+{
+    asm volatile("s_add_u32 m0, %0, %1" :: "s"(base), "n"(imm) : "m0", "scc");
+}
+__device__ __forceinline__ void async_copy16_m0(const void* base, uint32_t byte_off)
+{
+    asm volatile("global_load_lds_dwordx4 %0, %1" :: "v"(byte_off), "s"(base) : "memory");
+}
+
 __device__ __forceinline__ half8 lds_read_b128(uint32_t addr)
 {
     return *(__attribute__((address_space(3))) const half8*)(uintptr_t)addr;

@@ -207,6 +207,13 @@ __device__ __forceinline__ void pp_tile(const TiledParams& p, const uint32_t sme
         }
     };
 
+    // The same copies in two steps for the main loop: the LDS destination goes to M0 with one scalar
+    // add (a wave-uniform base plus an immediate), and the load follows one MFMA later -- the MFMA
+    // between them is the wait state an M0 write needs before an LDS-DMA load, so a copy costs
+    // the multiplying wavefront two issue slots instead of four.
+    auto a_dst_base = [&](int s, int half) -> uint32_t { return smem_base + A_REGION + (s & 1) * A_BUF + half * (A_BUF / 2) + 1024 * wn; };
+    auto b_dst_base = [&](int s, int half) -> uint32_t { return smem_base + B_REGION + (s % 3) * B_BUF + half * (B_BUF / 2) + 1024 * wn; };
+
     // X copies A-top and B-low, Y copies A-bottom and B-high: each group brings
     // in the A rows it reads itself and one k half of B for both groups.
     uint32_t a_off[4], b_off[4];
@@ -335,6 +342,12 @@ __device__ __forceinline__ void pp_tile(const TiledParams& p, const uint32_t sme
     auto multiply_phase = [&](int k, int h, auto copy_tag) {
         constexpr bool COPY = decltype(copy_tag)::value != 0;
         typedef BoolTag<decltype(copy_tag)::value == 1> whole_t;
+        const uint32_t dst_base = (h == 0) ? b_dst_base(k + 2, grp) : a_dst_base(k + 2, grp);
+        if constexpr (decltype(copy_tag)::value == 1 && NMFMA / 8 - 1 == 0) {
+            __builtin_amdgcn_sched_barrier(0);
+            set_m0(dst_base, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
 #pragma unroll
         for (int s = 0; s < NSL / 2; s++)
 #pragma unroll
@@ -345,7 +358,22 @@ __device__ __forceinline__ void pp_tile(const TiledParams& p, const uint32_t sme
                     if constexpr (MI == 32) acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[s][fn], fa[s][fm], acc[fm][fn], 0, 0, 0);
                     else                    acc[fm][fn] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fb[s][fn], fa[s][fm], acc[fm][fn], 0, 0, 0);
                     const int idx = (s * FM + fm) * FN + fn;
-                    if (COPY && idx % (NMFMA / 4) == NMFMA / 8 - 1) {
+                    if constexpr (decltype(copy_tag)::value == 1) {
+                        // whole k step: copy t is loaded behind MFMA t * NMFMA/4 + NMFMA/8 - 1 and its M0 is
+                        // set one MFMA earlier (copy 0 of the small tiles: in front of the first MFMA)
+                        const int tl = idx / (NMFMA / 4), ts = (idx + 1) / (NMFMA / 4);
+                        if (idx % (NMFMA / 4) == NMFMA / 8 - 1 && tl < (h == 0 ? TB : TA)) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (h == 0) async_copy16_m0(b_tile + ((int64_t)(k + 2) * BK + grp * 32) * p.ldb, b_off[tl]);
+                            else        async_copy16_m0(a_tile + (int64_t)(k + 2) * BK, a_off[tl]);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                        if ((idx + 1) % (NMFMA / 4) == NMFMA / 8 - 1 && ts < (h == 0 ? TB : TA)) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            set_m0(dst_base, 4096 * ts);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    } else if (COPY && idx % (NMFMA / 4) == NMFMA / 8 - 1) {
                         __builtin_amdgcn_sched_barrier(0);
                         if (h == 0) { if (idx / (NMFMA / 4) < TB) copy_b_part(k + 2, grp, b_off, idx / (NMFMA / 4), whole_t{}); }
                         else        { if (idx / (NMFMA / 4) < TA) copy_a_part(k + 2, grp, a_off, idx / (NMFMA / 4), whole_t{}); }
@@ -369,7 +397,10 @@ __device__ __forceinline__ void pp_tile(const TiledParams& p, const uint32_t sme
 #pragma unroll
         for (int h = 0; h < 2; h++) {
             read_fragments(k, h);          // X: phase 4k + 2h,     Y: 4k + 2h + 1
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            // lgkmcnt(0), as the builtin: the compiler then knows that the fragments have arrived
+            // and puts no waits of its own between the MFMAs that use them
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+            asm volatile("" ::: "memory");
             phase_barrier();
             multiply_phase(k, h, copy_tag);          // X: phase 4k + 2h + 1, Y: 4k + 2h + 2
             if (decltype(copy_tag)::value != 0 || grp == 0 || h == 0 || k + 1 < KT) phase_barrier();
