@@ -147,7 +147,8 @@ def time_gemm(binding, torch, mode, M, N, K, sets, steps, warmup):
     """Time `steps` launches; launch i works on sets[i % len(sets)] (one set: every
     launch re-reads the same operands, which the 256 MB last-level cache may still
     hold; several sets larger than that cache in total: every launch finds its
-    operands in HBM only).  Return (ms per step, list of per-launch ms, host ms)."""
+    operands in HBM only).  Return (ms per step, mean launch ms of each quarter of the
+    timed series, host ms per step)."""
     fn = binding.gemm_f16_f32acc if mode == "f32" else binding.gemm_f16_f16acc
     stream = torch.cuda.current_stream()
     sp = stream.cuda_stream
@@ -157,17 +158,21 @@ def time_gemm(binding, torch, mode, M, N, K, sets, steps, warmup):
     for i in range(warmup):
         a, b, c = sets[i % R]
         binding.check(fn(M, N, K, a, lda, b, ldb, c, ldc, sp))
-    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    # events at the quarter points only: an event between two launches costs a few microseconds,
+    # which is nothing for the headline and a third of the time of the smallest problems
+    marks = sorted({(steps * q) // 4 for q in range(5)})
+    evs = {m: torch.cuda.Event(enable_timing=True) for m in marks}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     evs[0].record(stream)
     for i in range(steps):
         a, b, c = sets[(warmup + i) % R]
         binding.check(fn(M, N, K, a, lda, b, ldb, c, ldc, sp))
-        evs[i + 1].record(stream)
+        if i + 1 in evs:
+            evs[i + 1].record(stream)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
-    per = [evs[i].elapsed_time(evs[i + 1]) for i in range(steps)]
+    per = [evs[a].elapsed_time(evs[b]) / (b - a) for a, b in zip(marks[:-1], marks[1:])]     # mean launch time per quarter
     total = evs[0].elapsed_time(evs[steps])
     return total / steps, per, wall_ms / steps
 
@@ -195,7 +200,9 @@ def main():
                     help="instead of the GEMM, run plain device-to-device copies of this many MiB "
                          "(calibration of the FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
     ap.add_argument("--sweep", action="store_true", help="also time every workload and the square sweep (extra lines on stderr)")
-    ap.add_argument("--force-config", type=int, default=-1)
+    ap.add_argument("--force-config", default="-1", metavar="ID|NAME",
+                    help="run this configuration of the library's table instead of the selected one")
+    ap.add_argument("--no-idle-leg", action="store_true", help="leave out the repeat of the protocol after an idle gap")
     ap.add_argument("--ladder", action="store_true", help="use libgemm_f16_ladder.so (for --force-config on a comparison kernel)")
     ap.add_argument("--rotate", default="auto", choices=["auto", "on", "off"],
                     help="launch i works on operand set i mod R (R sets, 1 GiB or more in total), so that no launch finds "
@@ -224,7 +231,13 @@ def main():
     if args.ladder:
         binding._active = "ladder"          # the library that also holds the comparison kernels (same selection)
     binding.load()
-    binding.force_config(args.force_config)
+    forced = args.force_config
+    if not forced.lstrip("-").isdigit():
+        names = [binding.describe_config(i)["name"] for i in range(binding.num_configs())]
+        if forced not in names:
+            sys.exit(f"bench.py: no configuration named {forced!r}; the table holds {names}")
+        forced = names.index(forced)
+    binding.force_config(int(forced))
     dev = torch.device("cuda:0")
 
     def prepare(name, mode, shape=None, rotate=False, host=None):
@@ -261,9 +274,8 @@ def main():
 
     def quarters(per):
         """Mean launch time of the first and of the last quarter of the timed series (as launched)."""
-        q = max(1, len(per) // 4)
-        return {"first_quarter_ms": round(sum(per[:q]) / q, 5), "last_quarter_ms": round(sum(per[-q:]) / q, 5),
-                "median_ms": round(sorted(per)[len(per) // 2], 5), "min_ms": round(min(per), 5)}
+        return {"first_quarter_ms": round(per[0], 5), "last_quarter_ms": round(per[-1], 5),
+                "quarter_means_ms": [round(x, 5) for x in per]}
 
     # A problem whose operands fit the 256 MB last-level cache a few times over is
     # timed on rotating operand sets (every launch reads from HBM); the figure with
@@ -285,8 +297,7 @@ def main():
     r_other = timed(prep_other, args.steps, args.warmup) if prep_other else None
     same_set = timed(prep_same, args.steps, args.warmup) if prep_same else None
     M, N, K = r["M"], r["N"], r["K"]
-    per = sorted(r["per"])
-    avg_launch_ms = sum(per) / len(per)
+    avg_launch_ms = r["ms"]             # HIP events around the timed launches on the launch stream / launches
     achieved = 2.0 * M * N * K / (avg_launch_ms * 1e-3) / 1e12
     t_mfma = 2.0 * M * N * K / (PEAK_F16_MFMA_TFLOPS * 1e12)
     t_hbm = r["bytes"] / (PEAK_HBM_GBS * 1e9)
@@ -302,7 +313,6 @@ def main():
     if r["cfg"].get("split_rows"):          # two launches: the time below is that of the pair
         kernels += " + " + kernel_symbol(binding.describe_config(r["cfg"]["id2"])["name"], args.mode, K)
     roofline.update({"kernel": kernels, "avg_launch_ms": round(avg_launch_ms, 5),
-                     "median_launch_ms": round(per[len(per) // 2], 5), "min_launch_ms": round(per[0], 5),
                      "algorithmic_bytes": r["bytes"], "flops": 2 * M * N * K})
 
     cpu = None
@@ -318,9 +328,11 @@ def main():
                "sample": f"first {nrows} of {M} rows of C (all {N} columns, full K={K}) of the same workload, "
                          f"binary64 triple loop incl. decoding B; host has {os.cpu_count()} logical CPUs"}
     # the same protocol once more after the GPU has been idle (under the CPU leg, or for a second)
-    if args.no_cpu:
-        time.sleep(1.0)
-    idle = timed(prep, args.steps, args.warmup)
+    idle = None
+    if not args.no_idle_leg:
+        if args.no_cpu:
+            time.sleep(1.0)
+        idle = timed(prep, args.steps, args.warmup)
 
     out = {
         "metric": "TFLOP/s (2MNK/time), f16 GEMM " + ("f32" if args.mode == "f32" else "f16") + "-accumulate, M=N=K=8192"
@@ -336,10 +348,11 @@ def main():
                                     "follows the MFMA-only leg and the warm-up launches without a pause (steady state)")},
         "roofline": roofline, "cpu_baseline": cpu,
         "series": quarters(r["per"]),
-        "after_idle": {"value": round(idle["tflops"], 2), "ms_per_step": round(idle["ms"], 5), **quarters(idle["per"]),
-                       "what": "the same W + K launches started right after the GPU sat idle (under the CPU leg): "
-                               "the transient of the part's power management, not the kernel"},
     }
+    if idle is not None:
+        out["after_idle"] = {"value": round(idle["tflops"], 2), "ms_per_step": round(idle["ms"], 5), **quarters(idle["per"]),
+                             "what": "the same W + K launches started right after the GPU sat idle (under the CPU leg, or "
+                                     "for a second): the transient of the part's power management, not the kernel"}
     if launches is not None:
         ceil = ceiling_result(*launches)
         ceil["value_over_ceiling"] = round(r["tflops"] / ceil["value"], 4)
