@@ -133,6 +133,39 @@ def mfma_only_ceiling(torch, np, wl, dist, K, seconds=0.045):
     return launches, cus
 
 
+def loop_budget(torch, np, wl, dist, K, seconds=0.03):
+    """bench_probe.hip's three hand-scheduled loops (MFMAs only; + the LDS fragment reads of the
+    library's main loop; + its global -> LDS copies from L2) on operands drawn from `dist`: TFLOP/s
+    of each, the second of two launches of about `seconds`."""
+    import ctypes
+    if not os.path.exists(PROBE_LIB):
+        build_probe()
+    lib = ctypes.CDLL(PROBE_LIB)
+    lib.bench_loop_budget.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    lib.bench_loop_budget.restype = ctypes.c_int
+    rng = np.random.default_rng(0)
+    data = torch.from_numpy(wl._draw(rng, (32768,), dist, K).astype(np.float16)).cuda()      # 64 KB
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    stream = torch.cuda.current_stream()
+    out = {}
+    for variant, name in ((0, "mfma_only"), (1, "with_lds_reads"), (2, "with_lds_reads_and_copies")):
+        iters = 2000
+        for rep in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            rc = lib.bench_loop_budget(data.data_ptr(), sink.data_ptr(), variant, iters, cus, stream.cuda_stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            if rc != 0:
+                raise RuntimeError(f"bench_loop_budget returned {rc}")
+            ms = e0.elapsed_time(e1)
+            if rep == 0:
+                iters = int(max(2000, seconds * 1e3 / max(ms / iters, 1e-7)))
+        out[name] = round(float(cus) * 8 * iters * 32 * 16384 / (ms * 1e-3) / 1e12, 1)
+    return out
+
+
 def ceiling_result(launches, cus):
     e0, e1, iters = launches[-1]
     ms = e0.elapsed_time(e1)
@@ -199,6 +232,9 @@ def main():
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="instead of the GEMM, run plain device-to-device copies of this many MiB "
                          "(calibration of the FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
+    ap.add_argument("--loop-budget", action="store_true",
+                    help="instead of the GEMM, run bench_probe.hip's three hand-scheduled loops (MFMAs only; + LDS "
+                         "fragment reads; + global -> LDS copies) on the workload's operand distribution")
     ap.add_argument("--sweep", action="store_true", help="also time every workload and the square sweep (extra lines on stderr)")
     ap.add_argument("--force-config", default="-1", metavar="ID|NAME",
                     help="run this configuration of the library's table instead of the selected one")
@@ -227,6 +263,13 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_probe_bytes_read_per_copy": n, "copy_probe_bytes_written_per_copy": n,
                           "copies": args.warmup + args.steps}))
+        return
+    if args.loop_budget:
+        dist, k = wl.WORKLOADS[args.workload][3], wl.WORKLOADS[args.workload][2]
+        res = loop_budget(torch, np, wl, dist, k)
+        print(json.dumps({"loop_budget": res, "unit": "TFLOP/s", "workload": args.workload, "operands": dist,
+                          "what": "32 v_mfma_f32_16x16x32_f16 per wavefront and iteration, two wavefronts per SIMD, "
+                                  "hand-scheduled: alone; + 8 ds_read_b128 and 8 ds_read_b64_tr_b16; + 4 global_load_lds_dwordx4 from L2"}))
         return
     if args.ladder:
         binding._active = "ladder"          # the library that also holds the comparison kernels (same selection)
