@@ -16,7 +16,8 @@
  *   - A, B, C are DEVICE pointers (memory of the current HIP device) owned by
  *     the caller.  A and B are only read; C is read once and written once.
  *     C must not overlap A or B.  The library allocates nothing and keeps no
- *     state between calls except the benchmarking override below.
+ *     state between calls except the benchmarking override below (and what it
+ *     has learnt once about the device: compute units, XCDs, clock rate).
  *   - lda, ldb, ldc are row pitches in ELEMENTS (lda >= K, ldb >= N,
  *     ldc >= N).  Elements between the row length and the pitch are never
  *     read for A and B beyond what an aligned 16-byte fetch inside a row's
@@ -25,7 +26,9 @@
  *     well).  A problem with M == 0 or N == 0 does nothing; K == 0 leaves C
  *     unchanged.  Pointers of any 2-byte (A, B, f16 C) / 4-byte (f32 C)
  *     alignment are accepted; the fastest kernels are used when A and B are
- *     16-byte aligned with lda, ldb multiples of 8 and K, N multiples of 8.
+ *     16-byte aligned with lda, ldb multiples of 8, K, N multiples of 8 and
+ *     all three pitches at most 2^22 elements (beyond that a slower kernel
+ *     with 64-bit addressing throughout runs).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     The call only enqueues work: it never synchronises the device, and the
  *     result is complete when the stream reaches the end of that work.
@@ -55,10 +58,15 @@ enum {
 /*
  * Mixed-precision mode (paper, section Mixed Precision Performance).
  * A: M x K f16, B: K x N f16, C: M x N f32, all row-major device memory.
- * Every product a*b is formed exactly and summed in f32 on the matrix units,
- * starting from the f32 value of C already in memory (the paper hoists the C
- * load in front of the k loop and the store behind it: section Generating
- * WMMA Ops and More).  The summation order over k is the kernel's own.
+ * Every product a*b is formed exactly and summed in f32 on the matrix units.
+ * C is read once and written once per element, outside the k loop (the paper
+ * hoists the C load and store out of it: section Generating WMMA Ops and
+ * More).  Where the old value of C enters the sum is the kernel's choice: the
+ * large-tile kernels sum the K products starting from zero and add C last
+ * (sum + C, one more f32 rounding at the end), the small-tile and any-shape
+ * kernels start the accumulators from C (C + sum).  The summation order over
+ * k is the kernel's own as well; results are bit-exact wherever every partial
+ * sum is exactly representable, and within the f32 rounding bound otherwise.
  */
 int gemm_f16_f32acc(int64_t M, int64_t N, int64_t K,
                     const void* A, int64_t lda,
@@ -116,6 +124,11 @@ int gemm_f16_f16acc_bias_act(int64_t M, int64_t N, int64_t K,
 const char* gemm_strerror(int code);
 
 /*
+ * Configuration ids index one table: the product library (libgemm_f16.so) holds
+ * the kernels the selector can pick; a second build of the same sources
+ * (libgemm_f16_ladder.so) appends comparison kernels and ablation rows behind
+ * them, which are only ever run by forcing their id.
+ *
  * Tile configuration report (the paper picks the best of several thread-block
  * and warp tile combinations per problem size: Evaluation section).  When the
  * tile count of the largest tile does not fill the last round of workgroups
@@ -156,10 +169,12 @@ int gemm_f16_describe_config(int id, gemm_f16_config* out);
 /*
  * Benchmarking aid: force configuration `id` for every later call of this
  * process (id < 0 restores automatic selection).  A forced configuration whose
- * alignment requirements the call does not meet is ignored for that call;
- * the launch forms made for several tiles per compute unit (names ending in
- * _chain, _stag, and the ov... kernel) run the plain 256 x 256 tiling on
- * problems they are not made for (few tiles, k tails, very short k loops).
+ * alignment or pitch requirements the call does not meet is ignored for that
+ * call.  The launch forms made for several tiles per compute unit (names
+ * ending in _chain and _stag) run the plain 256 x 256 tiling on problems with
+ * too few tiles for them (and _stag on devices other than 256 compute units);
+ * with a k tail (K not a multiple of 64) a forced _chain still runs chained,
+ * through its k-tail instantiation, which the selector itself does not pick.
  * Not thread-safe against concurrent GEMM calls.
  */
 int gemm_f16_force_config(int id);
