@@ -65,6 +65,7 @@ const GemmConfigDesc* pingpong_config();                             // gemm_pin
 const GemmConfigDesc* pingpong16_no_xcd_order_config();              // gemm_pingpong.hip: tiles dealt to XCDs as the hardware deals workgroups
 const GemmConfigDesc* tiled_no_swizzle_config();                     // gemm_tiled.hip: 256x256, LDS image not swizzled
 const GemmConfigDesc* generic_c_in_loop_config();                    // gemm_generic.hip: C read and written in every k step
+const GemmConfigDesc* generic_round_per_slice_config();              // gemm_generic.hip: f16 mode, running sum rounded to f16 every 16 k
 const GemmConfigDesc* interleaved_config();                          // ladder/gemm_interleaved.hip
 const GemmConfigDesc* overlap_config();                              // ladder/gemm_overlap.hip
 const GemmConfigDesc* w4_config();                                   // ladder/gemm_w4.hip

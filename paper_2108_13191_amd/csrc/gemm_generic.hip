@@ -15,7 +15,12 @@ constexpr int GBM = 64, GBN = 64, GBK = 32, GPAD = 8;
 // k step, as in the paper's Algorithm "Two-level tiled tensor core Matmul" before the load and
 // store of C are hoisted out of the k loop (section "Generating WMMA Ops and More").  With f16
 // C that rounds the running sum at every step, so the row is built for f32 C only.
-template <typename CT, bool C_IN_LOOP = false>
+// ROUND_PER_SLICE (another ladder row, f16 C only): the literal reading of the paper's half
+// precision mode (section Half Precision Performance: the accumulation is done in f16 as well)
+// -- the running sum is rounded to binary16, to nearest even, behind every MFMA, i.e. after
+// every 16-deep k slice, the depth of the paper's m16n16k16 operation.  The library's own
+// reading keeps the sum in f32 and rounds once at the store.
+template <typename CT, bool C_IN_LOOP = false, bool ROUND_PER_SLICE = false>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(
     int M, int N, int K, const half_t* __restrict__ A, int64_t lda,
     const half_t* __restrict__ B, int64_t ldb, CT* __restrict__ C, int64_t ldc, int tiles_n,
@@ -61,6 +66,10 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
             const half8 a = *reinterpret_cast<const half8*>(&As[wm * 32 + (lane & 31)][ks * 16 + 8 * (lane >> 5)]);
             const half8 b = *reinterpret_cast<const half8*>(&Bt[wn * 32 + (lane & 31)][ks * 16 + 8 * (lane >> 5)]);
             acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc, 0, 0, 0);
+            if constexpr (ROUND_PER_SLICE) {
+#pragma unroll
+                for (int i = 0; i < 16; i++) acc[i] = (float)(half_t)acc[i];
+            }
         }
         __syncthreads();
         if constexpr (C_IN_LOOP) {
@@ -112,6 +121,20 @@ int launch_generic_c_in_loop(const GemmArgs& a)
 const GemmConfigDesc kGenericCInLoop = {
     "generic64x64x32_c_in_loop", 64, 64, 32, 4, 32, 32, 2 * 64 * (32 + 8) * 2, false, launch_generic_c_in_loop, grid_generic};
 const GemmConfigDesc* generic_c_in_loop_config() { return &kGenericCInLoop; }
+
+int launch_generic_round_per_slice(const GemmArgs& a)
+{
+    if (!a.c_is_f16) return launch_generic(a);
+    const int64_t g = grid_generic(a.M, a.N);
+    if (g < 0) return GEMM_F16_ERR_SIZE;
+    const int tiles_n = (int)((a.N + GBN - 1) / GBN);
+    hipLaunchKernelGGL((gemm_generic_kernel<half_t, false, true>), dim3((unsigned)g), dim3(256), 0, a.stream,
+                       (int)a.M, (int)a.N, (int)a.K, a.A, a.lda, a.B, a.ldb, (half_t*)a.C, a.ldc, tiles_n, (const half_t*)a.bias, a.relu);
+    return hipGetLastError() == hipSuccess ? GEMM_F16_OK : GEMM_F16_ERR_LAUNCH;
+}
+const GemmConfigDesc kGenericRoundPerSlice = {
+    "generic64x64x32_f16_round_per_slice", 64, 64, 32, 4, 32, 32, 2 * 64 * (32 + 8) * 2, false, launch_generic_round_per_slice, grid_generic};
+const GemmConfigDesc* generic_round_per_slice_config() { return &kGenericRoundPerSlice; }
 #endif
 
 int launch_generic(const GemmArgs& a)

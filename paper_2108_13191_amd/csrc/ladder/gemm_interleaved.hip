@@ -1,18 +1,19 @@
-// The large-problem kernel, second form: 256 x 256 C tile per workgroup, 8
-// wavefronts of 128 x 64, k steps of 64, v_mfma_f32_16x16x32_f16 -- the same
-// tile, LDS image, copy plan and epilogue as the phase-alternating kernel
-// (gemm_pingpong.hip), but BOTH wavefronts of a SIMD multiply all the time.
+// A ladder row (comparison kernel, never selected): the 256 x 256 tile of the
+// phase-alternating kernel (gemm_pingpong.hip) -- same 8 wavefronts of 128 x 64,
+// k steps of 64, v_mfma_f32_16x16x32_f16, LDS image, copy plan and epilogue --
+// but BOTH wavefronts of a SIMD multiply all the time: every wavefront
+// software-pipelines its own fragment reads between its own MFMAs (the paper's
+// "Completing Latency Hiding" applied one level further down: LDS -> register
+// loads for a later block of MFMAs are in flight while the current block is
+// multiplied), and there is one barrier per k step instead of four.
 //
-// Why: one wavefront alone issues v_mfma_f32_16x16x32_f16 only every 19-22
-// cycles, two wavefronts of a SIMD together every 16 (measured with a loop of
-// nothing but MFMAs: 1.45 against 1.87 PFLOP/s on random operands).  In the
-// phase-alternating kernel one wavefront of each SIMD multiplies while the
-// other reads fragments, so its matrix pipe is issue-limited at about 0.8.
-// Here every wavefront software-pipelines its own fragment reads between its
-// own MFMAs (the paper's "Completing Latency Hiding" applied one level further
-// down: LDS -> register loads for a later block of MFMAs are in flight while
-// the current block is multiplied), and there is one barrier per k step
-// instead of four.
+// Outcome on the headline workload: 5-8 % slower than the phase-alternating
+// kernel (about 2650 against 2400 cycles per k step).  The older wavefront of a
+// SIMD wins the issue arbitration and reaches the barrier about 800 cycles
+// before the younger one, which finishes its k step alone; every LDS read,
+// copy, address add and wait of a wavefront sits between two of its own MFMAs;
+// and the part being power-limited, the less busy matrix pipe (0.67 against
+// 0.77) only partly turns into a higher clock (1.58 against 1.44 GHz).
 //
 // A k step of a wavefront is four blocks of 16 MFMAs (k slice s = 0, 1 of 32;
 // accumulator rows fm 0-3 or 4-7; all four accumulator columns):
@@ -27,6 +28,7 @@
 // two A buffers) are issued in block 3, the B copies for k+2 (three B buffers:
 // into the buffer of B(k-1)) in blocks 0 and 1.  Copies complete in order, so
 // "at most this k step's B copies outstanding" at the barrier means k+1 has landed.
+// K must be a multiple of 64 (k tails run the phase-alternating kernel).
 #include "../gemm_device.h"
 #include "../../../include/gemm_f16.h"
 

@@ -18,7 +18,8 @@ from gpu_util import run_gemm, assert_close, config_id       # noqa: E402
 
 CDT = {"f32": np.float32, "f16": np.float16}
 ROWS = ["t128x128x64_w2x2", "t256x256x64_w2x4", "t256x256x64_w2x4_noswz", "pp256x256x64_w2x4",
-        "pp256x256x64_w2x4_mi16_noxcd", "w4_256x256x64", "il256x256x64_w2x4_mi16", "generic64x64x32_c_in_loop"]
+        "pp256x256x64_w2x4_mi16_noxcd", "w4_256x256x64", "il256x256x64_w2x4_mi16", "generic64x64x32_c_in_loop",
+        "generic64x64x32_f16_round_per_slice"]
 SHAPES = [(64, 64, 64), (300, 264, 200), (520, 776, 136), (257, 8, 8), (1, 520, 72), (130, 136, 1000),
           (513, 264, 64), (256, 256, 8), (1100, 1296, 448)]
 
@@ -80,6 +81,40 @@ def test_rows_that_change_no_arithmetic_give_the_product_kernels_bits(oracle_mod
         out[name] = run_gemm(A, B, C0, "f32")
     assert np.array_equal(out["pp256x256x64_w2x4_mi16"], out["pp256x256x64_w2x4_mi16_noxcd"])
     assert np.array_equal(out["t256x256x64_w2x4"], out["t256x256x64_w2x4_noswz"])
+
+
+def test_f16_running_sum_rounded_every_16_k_matches_the_literal_reading(oracle_mod):
+    """The ladder row that rounds the running sum to binary16 after every 16-deep k slice against
+    the oracle's function for that reading of the paper's half-precision mode: bit for bit where
+    every slice sum is exact in f32 (integers, incl. sums beyond 2048, where binary16 rounds and
+    ties go to even), and on random data inside the f16 bar against the exact result, close to
+    the literal oracle (the matrix unit adds a slice in f32, the oracle exactly: a slice sum can
+    land on the other side of a binary16 rounding boundary now and then)."""
+    binding.force_config(config_id("generic64x64x32_f16_round_per_slice"))
+    # all ones: the running sum walks 16, 32, ... and sticks at 2048 + ties
+    for K in (2064, 4096):
+        A = np.ones((64, K), np.float16)
+        B = np.ones((K, 72), np.float16)
+        C0 = np.zeros((64, 72), np.float16)
+        C0[:, 1] = 1.0                     # odd running sums: ties on the way
+        got = run_gemm(A, B, C0, "f16")
+        want = oracle_mod.gemm_f16_rounding_every_slice(A, B, C0)
+        assert np.array_equal(got.astype(np.float64), want), f"all ones, K = {K}"
+    A, B, C0 = wl.make_inputs(200, 136, 2000, "int2", "int2", seed=9, c_dtype=np.float16)
+    got = run_gemm(A, B, C0, "f16")
+    want = oracle_mod.gemm_f16_rounding_every_slice(A, B, C0)
+    assert np.array_equal(got.astype(np.float64), want), "integers -2..2, K = 2000"
+    worst_lit, worst_ref = 0.0, 0.0
+    for K in (1024, 8192):
+        A, B, C0 = wl.make_inputs(130, 136, K, "normal_rsqrtk", "zeros", seed=K, c_dtype=np.float16)
+        got = run_gemm(A, B, C0, "f16").astype(np.float64)
+        Cref, S = oracle_mod.gemm_f16(A, B, C0)
+        lit = oracle_mod.gemm_f16_rounding_every_slice(A, B, C0)
+        assert np.all(np.abs(got - Cref) <= 4e-3 * S)
+        worst_ref = max(worst_ref, float(np.max(np.abs(got - Cref) / S)))
+        worst_lit = max(worst_lit, float(np.max(np.abs(got - lit) / S)))
+        assert np.mean(got == lit) > 0.9 and np.all(np.abs(got - lit) <= 1e-3 * S)
+    print(f"per-slice rounding on the GPU: worst |C - C_ref| / S = {worst_ref:.2e}, worst |C - literal oracle| / S = {worst_lit:.2e}")
 
 
 def test_the_four_wavefront_kernel_has_no_fused_epilogue():
