@@ -226,6 +226,8 @@ def main():
                     help="leave out the MFMA-only leg in front of the timed region (the timed launches then "
                          "start on an idle GPU and show the transient of its power management)")
     ap.add_argument("--workload", default="sq8192_normal")
+    ap.add_argument("--shape", default=None, metavar="M,N,K",
+                    help="instead of a named workload: this shape with A, B ~ U[-1,1] and C zero (as the square sweep's points)")
     ap.add_argument("--mode", default="f32", choices=["f32", "f16"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of C the oracle is timed on")
@@ -326,6 +328,10 @@ def main():
     def small(m, n, k, mode):
         return algorithmic_bytes(m, n, k, 4 if mode == "f32" else 2) < ROTATE_BELOW_BYTES
 
+    shape = tuple(int(x) for x in args.shape.split(",")) if args.shape else None
+    if shape:
+        args.workload = "shape" + "x".join(str(x) for x in shape)
+        wl.WORKLOADS[args.workload] = (*shape, "uniform", "zeros", ("f32", "f16"))
     m0, n0, k0 = wl.WORKLOADS[args.workload][:3]
     modes = wl.WORKLOADS[args.workload][5]
     other = {"f32": "f16", "f16": "f32"}[args.mode]
