@@ -137,13 +137,18 @@ const Cand kCands[] = {{ID_PP256, 1.0, 1}, {ID_PP192, 0.87, 1}, {ID_PP128, 0.78,
 // (the last round has fewer than 256 x per_cu of them) run somewhat faster.
 // The 128 x 128 form's two workgroups per compute unit hide each other's
 // prologue and epilogue, which counts for more the shorter the k loop is.
-double launch_cost(const Cand& c, int64_t M, int64_t N, int64_t K)
+// The 64 x 64 tiling moves f16 C two bytes per lane: on problems of 512^2 results and more with
+// k loops up to 2048 its f16 mode falls behind the 128 x 128 form (measured 25 / 62 / 78 / 123
+// against 29 / 75 / 104 / 146 TFLOP/s at 512^3, 768^3, 1024^2 x 512, 1024^3; in f32 mode, and at
+// K = 4096 in both, it stays ahead).
+double launch_cost(const Cand& c, int c_is_f16, int64_t M, int64_t N, int64_t K)
 {
     const GemmConfigDesc* d = config(c.id);
     const int64_t g = d->grid(M, N);
     if (g < 0) return -1.0;
     double eff = c.eff;
     if (c.id == ID_PP128x128) { eff = 0.78 + 0.2 * (K < 1024 ? 1.0 : 1024.0 / (double)K); if (eff > 0.92) eff = 0.92; }
+    if (c.id == ID_T64 && c_is_f16 && K <= 2048 && M * N >= 512 * 512) eff *= 0.75;
     const int64_t cus = chip().cus, slots = cus * c.per_cu;
     const int64_t full = g / slots, left = g % slots;
     const double sharing = (double)((left + cus - 1) / cus);                   // workgroups per compute unit in the last round
@@ -151,12 +156,12 @@ double launch_cost(const Cand& c, int64_t M, int64_t N, int64_t K)
     return ((double)full * c.per_cu + last) * (double)d->block_m * d->block_n / eff;
 }
 
-int best_single(int64_t M, int64_t N, int64_t K, double* cost_out)
+int best_single(int c_is_f16, int64_t M, int64_t N, int64_t K, double* cost_out)
 {
     int best = ID_PP256;
     double best_cost = -1.0;
     for (const Cand& c : kCands) {
-        const double cost = launch_cost(c, M, N, K);
+        const double cost = launch_cost(c, c_is_f16, M, N, K);
         if (cost < 0) continue;
         if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = c.id; }
     }
@@ -182,12 +187,12 @@ int chained_if_it_pays(int id, int64_t rows, int64_t N, int64_t K)
     return c->grid(rows, N) < config(ID_PP256)->grid(rows, N) ? id_chained() : id;
 }
 
-Plan select_plan_unchained(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, int64_t ldc)
+Plan select_plan_unchained(int c_is_f16, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, int64_t ldc)
 {
     if (!aligned_for_tiled(N, K, A, lda, B, ldb, ldc)) return {ID_GENERIC, M, -1};
     if (g_forced >= 0 && g_forced < num_configs()) return {g_forced, M, -1};
     double cost = 0;
-    Plan best = {best_single(M, N, K, &cost), M, -1};
+    Plan best = {best_single(c_is_f16, M, N, K, &cost), M, -1};
     const int64_t tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256, cus = chip().cus;
     if (tiles_n > cus || tiles_m < 2 || cost < 0) return best;
     // Short k loops, two or more full rounds of 256 x 256 tiles and a last round at
@@ -205,16 +210,16 @@ Plan select_plan_unchained(int64_t M, int64_t N, int64_t K, const void* A, int64
         const int64_t j = (r * cus) / tiles_n;             // tile rows that fit r rounds
         if (j < 1 || j >= tiles_m) continue;
         double rest = 0;
-        const int id2 = best_single(M - 256 * j, N, K, &rest);
+        const int id2 = best_single(c_is_f16, M - 256 * j, N, K, &rest);
         const double first = (double)((j * tiles_n + cus - 1) / cus) * 65536.0;
         if (rest >= 0 && first + rest + second_launch < cost) { cost = first + rest + second_launch; best = {ID_PP256, 256 * j, id2}; }
     }
     return best;
 }
 
-Plan select_plan(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, int64_t ldc)
+Plan select_plan(int c_is_f16, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, int64_t ldc)
 {
-    Plan pl = select_plan_unchained(M, N, K, A, lda, B, ldb, ldc);
+    Plan pl = select_plan_unchained(c_is_f16, M, N, K, A, lda, B, ldb, ldc);
     if (g_forced >= 0 && g_forced < num_configs()) return pl;        // a forced configuration runs as it is
     pl.id = chained_if_it_pays(pl.id, pl.rows1, N, K);
     if (pl.id2 >= 0) pl.id2 = chained_if_it_pays(pl.id2, M - pl.rows1, N, K);
@@ -253,7 +258,7 @@ int run(int c_is_f16, int64_t M, int64_t N, int64_t K, const void* A, int64_t ld
         a.c_is_f16 = c_is_f16; a.stream = (hipStream_t)stream;
         return config(ID_GENERIC)->launch(a);
     }
-    const Plan plan = select_plan(M, N, K, A, lda, B, ldb, ldc);
+    const Plan plan = select_plan(c_is_f16, M, N, K, A, lda, B, ldb, ldc);
     a.M = plan.rows1; a.N = N; a.K = K;
     a.A = (const half_t*)A; a.lda = lda; a.B = (const half_t*)B; a.ldb = ldb; a.C = C; a.ldc = ldc;
     a.c_is_f16 = c_is_f16; a.stream = (hipStream_t)stream;
@@ -319,7 +324,7 @@ int gemm_f16_query_config(int c_is_f16, int64_t M, int64_t N, int64_t K, const v
     const void* c = C ? C : (const void*)16;
     const int rc = check_args(c_is_f16, M, N, K, a, lda, b, ldb, c, ldc);
     if (rc != GEMM_F16_OK) return rc;
-    const Plan plan = select_plan(M, N, K, a, lda, b, ldb, ldc);
+    const Plan plan = select_plan(c_is_f16, M, N, K, a, lda, b, ldb, ldc);
     if (M == 0 || N == 0 || K == 0) { fill_desc(plan.id, 0, out); return GEMM_F16_OK; }
     int64_t g = config(plan.id)->grid(plan.rows1, N);
     if (g < 0) return GEMM_F16_ERR_SIZE;
