@@ -111,7 +111,7 @@ def mfma_only_ceiling(torch, np, wl, dist, K, seconds=0.045):
     lib.bench_mfma_only.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
     lib.bench_mfma_only.restype = ctypes.c_int
     rng = np.random.default_rng(0)
-    frags = torch.from_numpy(wl._draw(rng, (12 * 256, 8), dist, K).astype(np.float16)).cuda()
+    frags = torch.from_numpy(wl.draw(rng, (12 * 256, 8), dist, K).astype(np.float16)).cuda()
     sink = torch.zeros(1, dtype=torch.float32, device="cuda")
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     stream = torch.cuda.current_stream()
@@ -144,7 +144,7 @@ def loop_budget(torch, np, wl, dist, K, seconds=0.03):
     lib.bench_loop_budget.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
     lib.bench_loop_budget.restype = ctypes.c_int
     rng = np.random.default_rng(0)
-    data = torch.from_numpy(wl._draw(rng, (32768,), dist, K).astype(np.float16)).cuda()      # 64 KB
+    data = torch.from_numpy(wl.draw(rng, (32768,), dist, K).astype(np.float16)).cuda()      # 64 KB
     sink = torch.zeros(1, dtype=torch.float32, device="cuda")
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     stream = torch.cuda.current_stream()

@@ -24,7 +24,9 @@ WORKLOADS = {
 SQUARE_SWEEP = tuple(range(1024, 16384 + 1, 1024))  # uniform A, B; C0 zero; both modes
 
 
-def _draw(rng: np.random.Generator, shape, dist: str, K: int) -> np.ndarray:
+def draw(rng: np.random.Generator, shape, dist: str, K: int) -> np.ndarray:
+    """float64 values of the named distribution (the recipe of every operand here; bench.py's
+    MFMA-only and loop-budget legs draw their register operands from the workload's own)."""
     if dist == "uniform":
         x = rng.uniform(-1.0, 1.0, size=shape)
     elif dist == "int2":
@@ -55,7 +57,7 @@ def make_inputs(M: int, N: int, K: int, dist_ab: str, dist_c: str, seed: int = 0
 
     def padded(shape, dist, dtype, ld):
         rows, cols = shape
-        vals = _draw(rng, shape, dist, K).astype(dtype)
+        vals = draw(rng, shape, dist, K).astype(dtype)
         if ld is None or ld == cols:
             return np.ascontiguousarray(vals)
         if ld < cols:
