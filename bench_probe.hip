@@ -97,6 +97,24 @@ __global__ __launch_bounds__(512) void mfma_only_kernel(const half8* __restrict_
 #define LOOP_LDS_COPIES LOOP_BODY("ds_read_b128 v[200:203], v230 offset:0\n\t", "ds_read_b64_tr_b16 v[204:205], v231 offset:1024\n\t", "ds_read_b128 v[208:211], v230 offset:2048\n\t", "ds_read_b64_tr_b16 v[212:213], v231 offset:3072\n\t", "ds_read_b128 v[200:203], v230 offset:4096\n\t", "ds_read_b64_tr_b16 v[204:205], v231 offset:5120\n\t", "ds_read_b128 v[208:211], v230 offset:6144\n\t", "ds_read_b64_tr_b16 v[212:213], v231 offset:7168\n\t", "ds_read_b128 v[200:203], v230 offset:8192\n\t", "ds_read_b64_tr_b16 v[204:205], v231 offset:9216\n\t", "ds_read_b128 v[208:211], v230 offset:10240\n\t", "ds_read_b64_tr_b16 v[212:213], v231 offset:11264\n\t", "ds_read_b128 v[200:203], v230 offset:12288\n\t", "ds_read_b64_tr_b16 v[204:205], v231 offset:13312\n\t", "ds_read_b128 v[208:211], v230 offset:14336\n\t", "ds_read_b64_tr_b16 v[212:213], v231 offset:15360\n\t", "s_add_u32 m0, %0, 32768\n\t", "s_add_u32 m0, %0, 33792\n\t", "s_add_u32 m0, %0, 34816\n\t", "s_add_u32 m0, %0, 35840\n\t", "global_load_lds_dwordx4 v232, %1 offset:0\n\t", "global_load_lds_dwordx4 v232, %1 offset:1024\n\t", "global_load_lds_dwordx4 v232, %1 offset:2048\n\t", "global_load_lds_dwordx4 v232, %1 offset:3072\n\t") "s_waitcnt vmcnt(4) lgkmcnt(0)"
 #define LOOP_CLOBBERS "v0", "v1", "v2", "v3", "v4", "v5", "v6", "v7", "v8", "v9", "v10", "v11", "v12", "v13", "v14", "v15", "v16", "v17", "v18", "v19", "v20", "v21", "v22", "v23", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32", "v33", "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44", "v45", "v46", "v47", "v48", "v49", "v50", "v51", "v52", "v53", "v54", "v55", "v56", "v57", "v58", "v59", "v60", "v61", "v62", "v63", "v64", "v65", "v66", "v67", "v68", "v69", "v70", "v71", "v72", "v73", "v74", "v75", "v76", "v77", "v78", "v79", "v80", "v81", "v82", "v83", "v84", "v85", "v86", "v87", "v88", "v89", "v90", "v91", "v92", "v93", "v94", "v95", "v96", "v97", "v98", "v99", "v100", "v101", "v102", "v103", "v104", "v105", "v106", "v107", "v108", "v109", "v110", "v111", "v112", "v113", "v114", "v115", "v116", "v117", "v118", "v119", "v120", "v121", "v122", "v123", "v124", "v125", "v126", "v127", "v128", "v129", "v130", "v131", "v132", "v133", "v134", "v135", "v136", "v137", "v138", "v139", "v140", "v141", "v142", "v143", "v144", "v145", "v146", "v147", "v148", "v149", "v150", "v151", "v152", "v153", "v154", "v155", "v156", "v157", "v158", "v159", "v160", "v161", "v162", "v163", "v164", "v165", "v166", "v167", "v168", "v169", "v170", "v171", "v172", "v173", "v174", "v175", "v176", "v177", "v178", "v179", "v180", "v181", "v182", "v183", "v184", "v185", "v186", "v187", "v188", "v189", "v190", "v191", "v192", "v193", "v194", "v195", "v196", "v197", "v198", "v199", "v200", "v201", "v202", "v203", "v204", "v205", "v206", "v207", "v208", "v209", "v210", "v211", "v212", "v213", "v214", "v215", "v216", "v217", "v218", "v219", "v220", "v221", "v222", "v223", "v224", "v225", "v226", "v227", "v228", "v229"
 
+#define ZERO_ACCUMULATORS \
+    "v_mov_b32 v64, 0\n\tv_mov_b32 v65, 0\n\tv_mov_b32 v66, 0\n\tv_mov_b32 v67, 0\n\tv_mov_b32 v68, 0\n\tv_mov_b32 v69, 0\n\tv_mov_b32 v70, 0\n\tv_mov_b32 v71, 0\n\t" \
+    "v_mov_b32 v72, 0\n\tv_mov_b32 v73, 0\n\tv_mov_b32 v74, 0\n\tv_mov_b32 v75, 0\n\tv_mov_b32 v76, 0\n\tv_mov_b32 v77, 0\n\tv_mov_b32 v78, 0\n\tv_mov_b32 v79, 0\n\t" \
+    "v_mov_b32 v80, 0\n\tv_mov_b32 v81, 0\n\tv_mov_b32 v82, 0\n\tv_mov_b32 v83, 0\n\tv_mov_b32 v84, 0\n\tv_mov_b32 v85, 0\n\tv_mov_b32 v86, 0\n\tv_mov_b32 v87, 0\n\t" \
+    "v_mov_b32 v88, 0\n\tv_mov_b32 v89, 0\n\tv_mov_b32 v90, 0\n\tv_mov_b32 v91, 0\n\tv_mov_b32 v92, 0\n\tv_mov_b32 v93, 0\n\tv_mov_b32 v94, 0\n\tv_mov_b32 v95, 0\n\t" \
+    "v_mov_b32 v96, 0\n\tv_mov_b32 v97, 0\n\tv_mov_b32 v98, 0\n\tv_mov_b32 v99, 0\n\tv_mov_b32 v100, 0\n\tv_mov_b32 v101, 0\n\tv_mov_b32 v102, 0\n\tv_mov_b32 v103, 0\n\t" \
+    "v_mov_b32 v104, 0\n\tv_mov_b32 v105, 0\n\tv_mov_b32 v106, 0\n\tv_mov_b32 v107, 0\n\tv_mov_b32 v108, 0\n\tv_mov_b32 v109, 0\n\tv_mov_b32 v110, 0\n\tv_mov_b32 v111, 0\n\t" \
+    "v_mov_b32 v112, 0\n\tv_mov_b32 v113, 0\n\tv_mov_b32 v114, 0\n\tv_mov_b32 v115, 0\n\tv_mov_b32 v116, 0\n\tv_mov_b32 v117, 0\n\tv_mov_b32 v118, 0\n\tv_mov_b32 v119, 0\n\t" \
+    "v_mov_b32 v120, 0\n\tv_mov_b32 v121, 0\n\tv_mov_b32 v122, 0\n\tv_mov_b32 v123, 0\n\tv_mov_b32 v124, 0\n\tv_mov_b32 v125, 0\n\tv_mov_b32 v126, 0\n\tv_mov_b32 v127, 0\n\t" \
+    "v_mov_b32 v128, 0\n\tv_mov_b32 v129, 0\n\tv_mov_b32 v130, 0\n\tv_mov_b32 v131, 0\n\tv_mov_b32 v132, 0\n\tv_mov_b32 v133, 0\n\tv_mov_b32 v134, 0\n\tv_mov_b32 v135, 0\n\t" \
+    "v_mov_b32 v136, 0\n\tv_mov_b32 v137, 0\n\tv_mov_b32 v138, 0\n\tv_mov_b32 v139, 0\n\tv_mov_b32 v140, 0\n\tv_mov_b32 v141, 0\n\tv_mov_b32 v142, 0\n\tv_mov_b32 v143, 0\n\t" \
+    "v_mov_b32 v144, 0\n\tv_mov_b32 v145, 0\n\tv_mov_b32 v146, 0\n\tv_mov_b32 v147, 0\n\tv_mov_b32 v148, 0\n\tv_mov_b32 v149, 0\n\tv_mov_b32 v150, 0\n\tv_mov_b32 v151, 0\n\t" \
+    "v_mov_b32 v152, 0\n\tv_mov_b32 v153, 0\n\tv_mov_b32 v154, 0\n\tv_mov_b32 v155, 0\n\tv_mov_b32 v156, 0\n\tv_mov_b32 v157, 0\n\tv_mov_b32 v158, 0\n\tv_mov_b32 v159, 0\n\t" \
+    "v_mov_b32 v160, 0\n\tv_mov_b32 v161, 0\n\tv_mov_b32 v162, 0\n\tv_mov_b32 v163, 0\n\tv_mov_b32 v164, 0\n\tv_mov_b32 v165, 0\n\tv_mov_b32 v166, 0\n\tv_mov_b32 v167, 0\n\t" \
+    "v_mov_b32 v168, 0\n\tv_mov_b32 v169, 0\n\tv_mov_b32 v170, 0\n\tv_mov_b32 v171, 0\n\tv_mov_b32 v172, 0\n\tv_mov_b32 v173, 0\n\tv_mov_b32 v174, 0\n\tv_mov_b32 v175, 0\n\t" \
+    "v_mov_b32 v176, 0\n\tv_mov_b32 v177, 0\n\tv_mov_b32 v178, 0\n\tv_mov_b32 v179, 0\n\tv_mov_b32 v180, 0\n\tv_mov_b32 v181, 0\n\tv_mov_b32 v182, 0\n\tv_mov_b32 v183, 0\n\t" \
+    "v_mov_b32 v184, 0\n\tv_mov_b32 v185, 0\n\tv_mov_b32 v186, 0\n\tv_mov_b32 v187, 0\n\tv_mov_b32 v188, 0\n\tv_mov_b32 v189, 0\n\tv_mov_b32 v190, 0\n\tv_mov_b32 v191, 0\n\t"
+
 template <int VARIANT>
 __global__ __launch_bounds__(512) void loop_budget_kernel(const char* __restrict__ data /* 64 KB */, float* __restrict__ sink, int iters)
 {
@@ -120,6 +138,8 @@ __global__ __launch_bounds__(512) void loop_budget_kernel(const char* __restrict
                  "global_load_dwordx4 v[42:45], %0, off offset:160\n\tglobal_load_dwordx4 v[46:49], %0, off offset:176\n\t"
                  "s_waitcnt vmcnt(0)"
                  :: "v"(frag) : LOOP_CLOBBERS, "memory");
+    // accumulators start at zero (whatever a register held before would otherwise decide how much the adders toggle)
+    asm volatile(ZERO_ACCUMULATORS ::: LOOP_CLOBBERS);
     for (int it = 0; it < iters; it++) {
         if constexpr (VARIANT == 0) asm volatile(LOOP_MFMA_ONLY ::: LOOP_CLOBBERS, "memory");
         if constexpr (VARIANT == 1) asm volatile(LOOP_LDS ::: LOOP_CLOBBERS, "memory");
