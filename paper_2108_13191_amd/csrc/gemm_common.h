@@ -69,4 +69,5 @@ const GemmConfigDesc* generic_round_per_slice_config();              // gemm_gen
 const GemmConfigDesc* interleaved_config();                          // ladder/gemm_interleaved.hip
 const GemmConfigDesc* overlap_config();                              // ladder/gemm_overlap.hip
 const GemmConfigDesc* w4_config();                                   // ladder/gemm_w4.hip
+const GemmConfigDesc* w4a_config();                                  // ladder/gemm_w4a.hip: the same with its k loop in assembly
 #endif

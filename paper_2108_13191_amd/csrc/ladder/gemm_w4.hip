@@ -161,11 +161,12 @@ __global__ __launch_bounds__(256) void gemm_w4_kernel(const TiledParams p)
     auto c_ok = [&](int fm, int fn) -> bool {
         return !edge || ((c_row0 + fm * 16 + c_lrow < p.M) && (c_col0 + fn * 16 + c_lcol < p.N));
     };
-    // a group outside C reads the wavefront tile's first group instead (valid) and is not used
+    // a group outside C reads the first four elements of the workgroup's tile instead (always
+    // inside C; the wavefront's own 128 x 128 block may lie outside altogether) and is not used
     auto c_load = [&](int fm, int fn) -> ctx4 {
-        const char* base = reinterpret_cast<const char*>(Cbase + (int64_t)c_row0 * p.ldc + c_col0);
         const bool ok = c_ok(fm, fn);
-        const char* rowp = base + (ok ? (int64_t)fm * 16 * p.ldc * (int64_t)sizeof(CT) : 0);
+        const char* rowp = ok ? reinterpret_cast<const char*>(Cbase + (int64_t)(c_row0 + fm * 16) * p.ldc + c_col0)
+                              : reinterpret_cast<const char*>(Cbase + (int64_t)m0 * p.ldc + n0);
         const uint32_t off = ok ? c_voff + (uint32_t)(fn * 16 * sizeof(CT)) : 0u;
         return *reinterpret_cast<const ctx4*>(rowp + off);
     };
