@@ -107,6 +107,17 @@ __global__ __launch_bounds__(256) void gemm_w4a_kernel(const TiledParams p)
         }
     }
 
+    // Transposed 16 x 16 blocks (B fragment first): register r of lane l is row
+    // l%16, column 4*(l/16) + r of block (fm, fn): one vector access per block.
+    CT* const Cbase = (CT*)p.C;
+    typedef typename CVec4<CT>::type ctx4;
+    const int c_lrow = lane & 15, c_lcol = 4 * (lane >> 4);
+    const uint32_t c_voff = ((uint32_t)c_lrow * (uint32_t)p.ldc + (uint32_t)c_lcol) * (uint32_t)sizeof(CT);
+    const int c_row0 = m0 + wm_base, c_col0 = n0 + wn_base;
+    // C is read and added inside the loop where every load is a full, unmasked f32 access and
+    // the loop is long enough; otherwise behind it
+    const bool c_in_loop = sizeof(CT) == 4 && !edge && kt_full >= W4A_C_STEPS;
+
     floatx4 acc[8][8];
     if (kt_full > 0) {
         // k steps 0 and 1 into A buffers 0, 1 and B buffers 0, 1; the loop copies from k step 2 on
@@ -131,7 +142,13 @@ __global__ __launch_bounds__(256) void gemm_w4a_kernel(const TiledParams p)
         const uint32_t b_base_lo = __builtin_amdgcn_readfirstlane((uint32_t)b_base), b_base_hi = __builtin_amdgcn_readfirstlane((uint32_t)(b_base >> 32));
         const uint32_t a_ptr_lo = __builtin_amdgcn_readfirstlane((uint32_t)a_ptr), a_ptr_hi = __builtin_amdgcn_readfirstlane((uint32_t)(a_ptr >> 32));
         const uint32_t b_ptr_lo = __builtin_amdgcn_readfirstlane((uint32_t)b_ptr), b_ptr_hi = __builtin_amdgcn_readfirstlane((uint32_t)(b_ptr >> 32));
-        asm volatile(W4A_LOOP_ASM : W4A_LOOP_OUTPUTS(acc) : W4A_LOOP_INPUTS : W4A_LOOP_CLOBBERS);
+        const uint64_t c_wave = (uint64_t)(uintptr_t)(Cbase + (int64_t)c_row0 * p.ldc + c_col0);
+        const uint32_t c_lo = __builtin_amdgcn_readfirstlane((uint32_t)c_wave), c_hi = __builtin_amdgcn_readfirstlane((uint32_t)(c_wave >> 32));
+        const uint32_t c_rowstep = 16u * (uint32_t)p.ldc * (uint32_t)sizeof(CT);    // bytes from one row of blocks to the next (ldc <= 2^22)
+        if (c_in_loop)
+            asm volatile(W4A_LOOP_C_ASM : W4A_LOOP_OUTPUTS(acc) : W4A_LOOP_INPUTS : W4A_LOOP_CLOBBERS);
+        else
+            asm volatile(W4A_LOOP_ASM : W4A_LOOP_OUTPUTS(acc) : W4A_LOOP_INPUTS : W4A_LOOP_CLOBBERS);
     } else {
 #pragma unroll
         for (int fm = 0; fm < 8; fm++)
@@ -173,13 +190,6 @@ __global__ __launch_bounds__(256) void gemm_w4a_kernel(const TiledParams p)
     }
 
     // ---- + C, -> C -------------------------------------------------------------------
-    // Transposed 16 x 16 blocks (B fragment first): register r of lane l is row
-    // l%16, column 4*(l/16) + r of block (fm, fn): one vector access per block.
-    CT* const Cbase = (CT*)p.C;
-    typedef typename CVec4<CT>::type ctx4;
-    const int c_lrow = lane & 15, c_lcol = 4 * (lane >> 4);
-    const uint32_t c_voff = ((uint32_t)c_lrow * (uint32_t)p.ldc + (uint32_t)c_lcol) * (uint32_t)sizeof(CT);
-    const int c_row0 = m0 + wm_base, c_col0 = n0 + wn_base;
     auto c_ok = [&](int fm, int fn) -> bool {
         return !edge || ((c_row0 + fm * 16 + c_lrow < p.M) && (c_col0 + fn * 16 + c_lcol < p.N));
     };
@@ -214,6 +224,20 @@ __global__ __launch_bounds__(256) void gemm_w4a_kernel(const TiledParams p)
         }
     };
     auto fence = [&]() { __builtin_amdgcn_sched_barrier(0); };
+    if (c_in_loop) {                 // never an edge tile: every store is inside C
+#pragma unroll
+        for (int fm = 0; fm < 8; fm++) {
+            char* rowp = reinterpret_cast<char*>(Cbase + (int64_t)(c_row0 + fm * 16) * p.ldc + c_col0);
+#pragma unroll
+            for (int fn = 0; fn < 8; fn++) {
+                ctx4 v;
+#pragma unroll
+                for (int e = 0; e < 4; e++) v[e] = (CT)acc[fm][fn][e];
+                *reinterpret_cast<ctx4*>(rowp + c_voff + fn * 16 * sizeof(CT)) = v;
+            }
+        }
+        return;
+    }
     ctx4 c_q0[2][8], c_q1[2][8], c_q2[2][8];
     fetch_rows(0, c_q0); fetch_rows(2, c_q1); fetch_rows(4, c_q2); fence();
     finish_rows(0, c_q0); fence();

@@ -132,6 +132,26 @@ def test_assembly_k_loop_at_every_exit_of_its_six_step_body(oracle_mod):
             assert np.array_equal(got, oracle_mod.round_to_f32(Cref)), f"K = {K}"
 
 
+def test_c_read_inside_the_assembly_loop(oracle_mod):
+    """In f32 mode, on tiles that lie wholly inside C and with 18 or more full k steps, the
+    four-wavefront kernel reads C during its first 18 k steps and adds it to the running sums
+    there.  Shapes with interior and edge tiles side by side, 18 to 31 full k steps, with and
+    without a k tail, a C pitch that is not N: integers bit for bit, random data to tolerance
+    (both modes: f16 takes the path that adds C behind the loop)."""
+    binding.force_config(config_id("w4a_256x256x64"))
+    for idx, (M, N, K) in enumerate([(256, 256, 1152), (512, 768, 1216), (600, 520, 1280 + 24), (256, 512, 1984), (768, 300, 1408)]):
+        A, B, _ = wl.make_inputs(M, N, K, "int2", "zeros", seed=950 + idx)
+        C0 = np.random.default_rng(idx).integers(-4, 5, size=(M, N)).astype(np.float32)
+        got = run_gemm(A, B, C0, "f32", ldc=N + 8 * idx)
+        Cref, _ = oracle_mod.gemm_f16(A, B, C0)
+        assert np.array_equal(got, oracle_mod.round_to_f32(Cref)), f"ints {(M, N, K)}"
+        for mode in ("f32", "f16"):
+            A, B, C0 = wl.make_inputs(M, N, K, "uniform", "uniform", seed=960 + idx, c_dtype=CDT[mode])
+            got = run_gemm(A, B, C0, mode)
+            Cref, S = oracle_mod.gemm_f16(A, B, C0)
+            assert_close(got, Cref, S, C0, mode, what=f"w4a, C in the loop {(M, N, K)} {mode}")
+
+
 @pytest.mark.parametrize("name", ["w4_256x256x64", "w4a_256x256x64"])
 def test_the_four_wavefront_kernels_have_no_fused_epilogue(name):
     binding.force_config(config_id(name))

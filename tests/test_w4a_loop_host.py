@@ -3,10 +3,15 @@
 writes, and an emulation of the loop's scalar side (pointer arithmetic with carries, selects,
 branches) for 1..40 k steps shows that every copy fetches a k step below KT from the right
 address into the right LDS buffer, that every fragment read touches the buffer that holds its
-k step, and that the waits and barriers order copies and reads of a buffer."""
+k step, and that the waits and barriers order copies and reads of a buffer; for the block that
+reads C inside the loop, that every 16 x 16 block of C is loaded once from its address and added
+once to each of its four accumulator registers, after the load has landed, before the register
+set is loaded again, and never next to an MFMA of that block."""
 import importlib.util
 import os
 import re
+
+import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 GEN = os.path.join(ROOT, "paper_2108_13191_amd", "csrc", "ladder", "gen_w4a_loop.py")
@@ -28,6 +33,8 @@ def test_committed_include_is_what_the_generator_writes():
 A_BASE = 0x100000000 - 4096        # the running A pointer crosses a 32-bit carry
 B_BASE = 0x7000000000
 B_STEP = 64 * 8192 * 2
+C_BASE = 0x300000000 - 3 * 16 * 8192 * 4 - 64      # the C row pointer crosses a 32-bit carry
+C_ROWSTEP = 16 * 8192 * 4
 LDS_WAVE = 3072
 
 
@@ -39,6 +46,7 @@ def _run(lines, kt):
          "%[b_base_lo]": B_BASE & 0xffffffff, "%[b_base_hi]": B_BASE >> 32}
     ap, bp = A_BASE + 2 * 128, B_BASE + 2 * B_STEP
     S.update({"%[a_ptr_lo]": ap & 0xffffffff, "%[a_ptr_hi]": ap >> 32, "%[b_ptr_lo]": bp & 0xffffffff, "%[b_ptr_hi]": bp >> 32})
+    S.update({"%[c_lo]": C_BASE & 0xffffffff, "%[c_hi]": C_BASE >> 32, "%[c_rowstep]": C_ROWSTEP})
 
     def val(x):
         return S[x] if x in S else int(x)
@@ -72,10 +80,25 @@ def _run(lines, kt):
             m = re.match(r"s\[(\d+):(\d+)\]", a[1])
             src = S[f"s{m.group(1)}"] | (S[f"s{m.group(2)}"] << 32)
             trace.append((t, "copy", a[0], src, S["m0"], nmfma))
+        elif op == "global_load_dwordx4":
+            m = re.match(r"v\[(\d+):(\d+)\]", a[0])
+            m2 = re.match(r"s\[(\d+):(\d+)\] offset:(\d+)", a[2])
+            assert a[1] == "%[c_voff]" and int(m.group(2)) == int(m.group(1)) + 3
+            src = (S[f"s{m2.group(1)}"] | (S[f"s{m2.group(2)}"] << 32)) + int(m2.group(3))
+            trace.append((t, "cload", int(m.group(1)), src, nmfma))
+        elif op == "v_accvgpr_read_b32":
+            trace.append((t, "accread", a[0], int(a[1][1:]), nmfma))
+        elif op == "v_add_f32":
+            assert a[0] == a[1]
+            trace.append((t, "add", a[0], int(a[2][1:]), nmfma))
+        elif op == "v_accvgpr_write_b32" and a[1] != "0":
+            trace.append((t, "accwrite", int(a[0][1:]), a[1], nmfma))
         elif op.startswith("ds_read"):
             m = re.match(r"(%\[\w+\]) offset:(\d+)", a[1])
             trace.append((t, "read", m.group(1), int(m.group(2)), nmfma))
         elif op.startswith("v_mfma"):
+            m = re.match(r"a\[(\d+):", a[0])
+            trace.append((t, "mfma", int(m.group(1)) // 4))
             nmfma += 1
         elif op == "s_barrier":
             trace.append((t, "barrier"))
@@ -88,10 +111,13 @@ def _run(lines, kt):
     return trace, nmfma
 
 
-def test_scalar_side_of_the_loop_for_every_trip_count():
-    lines = _generator().block()
-    for kt in range(1, 41):
+@pytest.mark.parametrize("with_c", [False, True])
+def test_scalar_side_of_the_loop_for_every_trip_count(with_c):
+    gen = _generator()
+    lines = gen.block_c() if with_c else gen.block()
+    for kt in range(gen.C_STEPS if with_c else 1, gen.C_STEPS + 14 if with_c else 41):
         trace, nmfma = _run(lines, kt)
+        _check_c(gen, trace, with_c)
         assert nmfma == 128 * kt
         barriers = [e[0] for e in trace if e[1] == "barrier"]
         assert len(barriers) == kt
@@ -118,13 +144,15 @@ def test_scalar_side_of_the_loop_for_every_trip_count():
         landed = {("A", 0): 0, ("B", 0): 0}
         if kt > 1:
             landed.update({("A", 1): 1, ("B", 1): 1})
-        # --- a copy has landed for every wavefront once a wait that leaves fewer copies
-        # outstanding than were issued after it is followed by a barrier
+        # --- a copy has landed for every wavefront once a wait that leaves fewer vector-memory
+        # operations outstanding than were issued after it is followed by a barrier
+        vmem = [e[0] for e in trace if e[1] in ("copy", "cload")]
+
         def landed_at(copy_index):
             t_issue = copies[copy_index][0]
             for e in trace:
                 if e[1] == "wait" and e[2] is not None and e[0] > t_issue:
-                    later = sum(1 for c in copies if t_issue < c[0] < e[0])
+                    later = sum(1 for v in vmem if t_issue < v < e[0])
                     if later >= e[2]:
                         nxt = [b for b in barriers if b > e[0]]
                         return nxt[0] if nxt else None
@@ -161,3 +189,39 @@ def test_scalar_side_of_the_loop_for_every_trip_count():
             if after:
                 waits = [w[0] for w in trace if w[1] == "wait" and w[3] == 0 and w[0] > t]
                 assert waits and any(waits[0] < b < after[0][0] for b in barriers), ("buffer overwritten while read", kt, step, buf)
+
+
+def _check_c(gen, trace, with_c):
+    """The loads of C and their additions to the accumulators."""
+    loads = [e for e in trace if e[1] == "cload"]
+    if not with_c:
+        assert not loads and not any(e[1] in ("accread", "add", "accwrite") for e in trace)
+        return
+    assert len(loads) == 64
+    vmem = [e[0] for e in trace if e[1] in ("copy", "cload")]
+    waits = [e for e in trace if e[1] == "wait" and e[2] is not None]
+    mfmas = [e for e in trace if e[1] == "mfma"]
+    adds_seen = set()
+    for b, (t_load, _, reg, src, _) in enumerate(loads):
+        assert src == C_BASE + (b >> 3) * C_ROWSTEP + (b & 7) * 64, ("C source", b)
+        # landed: a wait behind the load that leaves no more outstanding than were issued after the load
+        t_landed = min(w[0] for w in waits if w[0] > t_load and sum(1 for v in vmem if t_load < v < w[0]) >= w[2])
+        # the next load into these registers
+        again = [l[0] for l in loads if l[2] == reg and l[0] > t_load]
+        t_again = again[0] if again else float("inf")
+        for e in range(4):
+            a_reg = 4 * b + e
+            rd = [x for x in trace if x[1] == "accread" and x[3] == a_reg]
+            wr = [x for x in trace if x[1] == "accwrite" and x[2] == a_reg]
+            assert len(rd) == 1 and len(wr) == 1, ("one addition per accumulator register", a_reg)
+            ad = [x for x in trace if x[1] == "add" and x[0] == rd[0][0] + 1]
+            assert len(ad) == 1 and ad[0][2] == rd[0][2] and ad[0][3] == reg + e and wr[0][0] == ad[0][0] + 1 and wr[0][3] == rd[0][2]
+            assert t_landed < ad[0][0] < t_again, ("C data not there / overwritten", b, e)
+            # no MFMA of block b between the read and the write, none issued within 5 MFMAs before the
+            # read, none within 2 MFMAs after the write
+            own = [m[0] for m in mfmas if m[2] == b]
+            before = [m[0] for m in mfmas if m[0] < rd[0][0]][-5:]
+            after = [m[0] for m in mfmas if m[0] > wr[0][0]][:2]
+            assert not any(before[0] <= o <= after[-1] for o in own), ("addition next to an MFMA of its block", b, e)
+            adds_seen.add(a_reg)
+    assert adds_seen == set(range(256))
