@@ -557,18 +557,6 @@ __device__ __forceinline__ void pp_tile(const TiledParams& p, const uint32_t sme
 // ends after 20 000 polls whatever the clock says) and changes no result.
 __device__ __forceinline__ void late_start(const TiledParams& p)
 {
-#ifdef EXP_GRADED
-    if ((int)blockIdx.x < p.first_generation) {
-        const uint64_t t0 = wall_clock64();
-#ifdef EXP_INTRA
-        const uint64_t ticks = (uint64_t)EXP_GRADED * (blockIdx.x % 8) + (uint64_t)EXP_INTRA * ((blockIdx.x / 64) % 4);
-#else
-        const uint64_t ticks = (uint64_t)EXP_GRADED * (blockIdx.x % 8);
-#endif
-        for (int spins = 0; wall_clock64() - t0 < ticks && spins < 20000; spins++) __builtin_amdgcn_s_sleep(16);
-        return;
-    }
-#endif
     if (p.stagger_ticks > 0 && (blockIdx.x & 1) && (int)blockIdx.x < p.first_generation) {
         const uint64_t t0 = wall_clock64();
         for (int spins = 0; wall_clock64() - t0 < (uint64_t)p.stagger_ticks && spins < 20000; spins++) __builtin_amdgcn_s_sleep(16);

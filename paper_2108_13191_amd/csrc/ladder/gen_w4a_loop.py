@@ -53,7 +53,7 @@ B_BUF = 32768
 B_REGION = 2 * A_BUF
 B_ROW = 512
 
-C_PER_STEP = 4                      # blocks of C loaded per k step in the C section
+C_PER_STEP = 2                      # blocks of C loaded per k step in the C section
 C_LOAD_STEPS = 64 // C_PER_STEP     # k steps that load C
 C_STEPS = ((C_LOAD_STEPS + 2 + 5) // 6) * 6   # length of the section: the last loads are added two steps later
 

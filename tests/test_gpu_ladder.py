@@ -133,13 +133,13 @@ def test_assembly_k_loop_at_every_exit_of_its_six_step_body(oracle_mod):
 
 
 def test_c_read_inside_the_assembly_loop(oracle_mod):
-    """In f32 mode, on tiles that lie wholly inside C and with 18 or more full k steps, the
-    four-wavefront kernel reads C during its first 18 k steps and adds it to the running sums
-    there.  Shapes with interior and edge tiles side by side, 18 to 31 full k steps, with and
+    """In f32 mode, on tiles that lie wholly inside C and with enough full k steps (a few dozen),
+    the four-wavefront kernel reads C during its first k steps and adds it to the running sums
+    there.  Shapes with interior and edge tiles side by side, 40 to 51 full k steps, with and
     without a k tail, a C pitch that is not N: integers bit for bit, random data to tolerance
     (both modes: f16 takes the path that adds C behind the loop)."""
     binding.force_config(config_id("w4a_256x256x64"))
-    for idx, (M, N, K) in enumerate([(256, 256, 1152), (512, 768, 1216), (600, 520, 1280 + 24), (256, 512, 1984), (768, 300, 1408)]):
+    for idx, (M, N, K) in enumerate([(256, 256, 2560), (512, 768, 2624), (600, 520, 2688 + 24), (256, 512, 3264), (768, 300, 2816)]):
         A, B, _ = wl.make_inputs(M, N, K, "int2", "zeros", seed=950 + idx)
         C0 = np.random.default_rng(idx).integers(-4, 5, size=(M, N)).astype(np.float32)
         got = run_gemm(A, B, C0, "f32", ldc=N + 8 * idx)
