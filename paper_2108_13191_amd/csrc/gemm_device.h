@@ -157,68 +157,12 @@ __device__ __forceinline__ void store_c_tile(const floatx16 (&acc)[FM][FN], CT* 
         }
 }
 
-// The same for accumulators formed with the operands exchanged (B fragment
-// first): the 32 x 32 block is then held transposed -- register i of lane l is
-// row l%32, column 8*(i/4) + 4*(l/32) + i%4 of its block, i.e. a lane owns 4
-// consecutive columns of one row of C per register group, and C moves 4
-// elements per lane and instruction (N is a multiple of 8 here, so such a
-// group lies entirely inside or outside C).  The load has a single
-// straight-line form: a group outside C reads the block's first group instead
-// (a valid address) and is replaced by zeros, so that all loads can be in
-// flight together.  Vector accesses are only element-aligned.
+// Accumulators formed with the operands exchanged (B fragment first) hold their block
+// transposed: a lane owns 4 consecutive columns of one row of C per register group, so C moves
+// 4 elements per lane and instruction (N is a multiple of 8 in the kernels that do this, so
+// such a group lies entirely inside or outside C).  Vector accesses are only element-aligned.
 template <typename CT> struct CVec4 {
     typedef CT type __attribute__((ext_vector_type(4), aligned(sizeof(CT))));
 };
-
-template <typename CT, int FM, int FN>
-__device__ __forceinline__ void load_c_tile_t(floatx16 (&acc)[FM][FN], const CT* C, int64_t ldc,
-                                              int row0, int col0, int lane, int M, int N, bool edge)
-{
-    typedef typename CVec4<CT>::type ctx4;
-    const int lrow = lane & 31, lcol = 4 * (lane >> 5);
-    const uint32_t voff = ((uint32_t)lrow * (uint32_t)ldc + (uint32_t)lcol) * (uint32_t)sizeof(CT);
-#pragma unroll
-    for (int fm = 0; fm < FM; fm++) {
-        // at most two accumulator rows (128 registers) of loads in flight at a time
-        if (fm > 0 && fm % 2 == 0) __builtin_amdgcn_sched_barrier(0);
-        const char* rowp = reinterpret_cast<const char*>(C + (int64_t)(row0 + fm * 32) * ldc + col0);
-        const bool row_ok = !edge || (row0 + fm * 32 + lrow < M);
-#pragma unroll
-        for (int fn = 0; fn < FN; fn++)
-#pragma unroll
-            for (int g = 0; g < 4; g++) {
-                const bool ok = row_ok && (!edge || (col0 + fn * 32 + 8 * g + lcol < N));
-                const uint32_t off = ok ? voff + (uint32_t)((fn * 32 + 8 * g) * sizeof(CT)) : 0u;
-                const ctx4 v = *reinterpret_cast<const ctx4*>(reinterpret_cast<const char*>(C + (int64_t)row0 * ldc + col0) + (ok ? (int64_t)fm * 32 * ldc * (int64_t)sizeof(CT) : 0) + off);
-                (void)rowp;
-#pragma unroll
-                for (int e = 0; e < 4; e++) acc[fm][fn][4 * g + e] = ok ? (float)v[e] : 0.0f;
-            }
-    }
-}
-
-template <typename CT, int FM, int FN>
-__device__ __forceinline__ void store_c_tile_t(const floatx16 (&acc)[FM][FN], CT* C, int64_t ldc,
-                                               int row0, int col0, int lane, int M, int N, bool edge)
-{
-    typedef typename CVec4<CT>::type ctx4;
-    const int lrow = lane & 31, lcol = 4 * (lane >> 5);
-    const uint32_t voff = ((uint32_t)lrow * (uint32_t)ldc + (uint32_t)lcol) * (uint32_t)sizeof(CT);
-#pragma unroll
-    for (int fm = 0; fm < FM; fm++) {
-        char* rowp = reinterpret_cast<char*>(C + (int64_t)(row0 + fm * 32) * ldc + col0);
-        const bool row_ok = !edge || (row0 + fm * 32 + lrow < M);
-#pragma unroll
-        for (int fn = 0; fn < FN; fn++)
-#pragma unroll
-            for (int g = 0; g < 4; g++) {
-                ctx4 v;
-#pragma unroll
-                for (int e = 0; e < 4; e++) v[e] = (CT)acc[fm][fn][4 * g + e];           // f16: one rounding, to nearest even
-                if (row_ok && (!edge || (col0 + fn * 32 + 8 * g + lcol < N)))
-                    *reinterpret_cast<ctx4*>(rowp + voff + (fn * 32 + 8 * g) * sizeof(CT)) = v;
-            }
-    }
-}
 
 }  // namespace gemm_dev
