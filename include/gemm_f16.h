@@ -64,7 +64,9 @@ enum {
  * More).  Where the old value of C enters the sum is the kernel's choice: the
  * large-tile kernels sum the K products starting from zero and add C last
  * (sum + C, one more f32 rounding at the end), the small-tile and any-shape
- * kernels start the accumulators from C (C + sum).  The summation order over
+ * kernels start the accumulators from C (C + sum), and the long-k kernel adds
+ * C to the running sum while its first few dozen k steps are being summed
+ * ((partial sum + C) + rest; on edge tiles it adds C last).  The summation order over
  * k is the kernel's own as well; results are bit-exact wherever every partial
  * sum is exactly representable, and within the f32 rounding bound otherwise.
  */

@@ -22,6 +22,7 @@ enum {
     ID_CHAIN,          // 256 x 256, one workgroup per compute unit walks its tiles
     ID_STAG,           // 256 x 256, every other compute unit starts on half a tile
     ID_T64,            // 64 x 64, four LDS stages
+    ID_LONG_K,         // 256 x 256, four wavefronts of 128 x 128, k loop in assembly
     NUM_PRODUCT
 };
 
@@ -30,7 +31,7 @@ const GemmConfigDesc kGeneric = {
     false, launch_generic, grid_generic};
 
 #ifdef GEMM_F16_LADDER
-constexpr int NUM_LADDER = 11;
+constexpr int NUM_LADDER = 10;
 #else
 constexpr int NUM_LADDER = 0;
 #endif
@@ -48,6 +49,7 @@ const GemmConfigDesc* config(int id)
     case ID_CHAIN:     return pingpong16_persistent_config();
     case ID_STAG:      return pingpong16_staggered_config();
     case ID_T64:       return tiled_config(64);
+    case ID_LONG_K:    return long_k_config();
 #ifdef GEMM_F16_LADDER
     case NUM_PRODUCT + 0: return tiled_config(128);
     case NUM_PRODUCT + 1: return tiled_config(256);
@@ -59,7 +61,6 @@ const GemmConfigDesc* config(int id)
     case NUM_PRODUCT + 7: return interleaved_config();
     case NUM_PRODUCT + 8: return generic_c_in_loop_config();
     case NUM_PRODUCT + 9: return generic_round_per_slice_config();
-    case NUM_PRODUCT + 10: return w4a_config();
 #endif
     default: return &kGeneric;
     }
@@ -188,6 +189,19 @@ int chained_if_it_pays(int id, int64_t rows, int64_t N, int64_t K)
     return c->grid(rows, N) < config(ID_PP256)->grid(rows, N) ? id_chained() : id;
 }
 
+// Long k loops take the four-wavefront kernel.  Measured against the chained 256 x 256 form,
+// both alternating in one process at the steady state (f32 / f16 mode): K = 16384: 16384^3
+// +3.5 ... +4.4 / +2.5 %, 8192^2 +1.3 ... +4 / +2 ... +4 %, 6144 x 8192 +2 / +2 %; K = 12288:
+// 12288^3 +1 ... +5 / +2 %, 16384^2 +1 ... +1.7 / +1 %, 8192 x 16384 0 %, 8192^2 -1 / 0 %;
+// K = 8192: 4096^2 (one tile per compute unit) +4.4 / +0.5 %, 4096 x 8192 +2 / 0 %, 8192^2
+// -0.5 ... -1 %, 12288^2 -1 ... -2 %, 16384^2 0 %; K = 4096: -1 ... -10 %.
+int long_k_if_it_pays(int id, int64_t rows, int64_t N, int64_t K)
+{
+    if (id != ID_PP256 && id != ID_CHAIN) return id;
+    const int64_t tiles = config(ID_PP256)->grid(rows, N);
+    return (K >= 12288 || (K >= 8192 && tiles <= 2 * (int64_t)chip().cus)) ? ID_LONG_K : id;
+}
+
 Plan select_plan_unchained(int c_is_f16, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, int64_t ldc)
 {
     if (!aligned_for_tiled(N, K, A, lda, B, ldb, ldc)) return {ID_GENERIC, M, -1};
@@ -222,8 +236,8 @@ Plan select_plan(int c_is_f16, int64_t M, int64_t N, int64_t K, const void* A, i
 {
     Plan pl = select_plan_unchained(c_is_f16, M, N, K, A, lda, B, ldb, ldc);
     if (g_forced >= 0 && g_forced < num_configs()) return pl;        // a forced configuration runs as it is
-    pl.id = chained_if_it_pays(pl.id, pl.rows1, N, K);
-    if (pl.id2 >= 0) pl.id2 = chained_if_it_pays(pl.id2, M - pl.rows1, N, K);
+    pl.id = long_k_if_it_pays(chained_if_it_pays(pl.id, pl.rows1, N, K), pl.rows1, N, K);
+    if (pl.id2 >= 0) pl.id2 = long_k_if_it_pays(chained_if_it_pays(pl.id2, M - pl.rows1, N, K), M - pl.rows1, N, K);
     return pl;
 }
 

@@ -59,6 +59,9 @@ const GemmConfigDesc* pingpong16_config(int block_m, int block_n);   // 256x256,
 const GemmConfigDesc* pingpong16_persistent_config();                 // 256x256, one workgroup per compute unit walks its tiles
 const GemmConfigDesc* pingpong16_staggered_config();                  // 256x256, every other compute unit half a tile ahead
 
+// gemm_w4a.hip
+const GemmConfigDesc* long_k_config();                                // 256x256, four wavefronts of 128x128, k loop in assembly
+
 #ifdef GEMM_F16_LADDER
 // Comparison kernels and ablation rows: built into libgemm_f16_ladder.so only, never selected.
 const GemmConfigDesc* pingpong_config();                             // gemm_pingpong.hip: 256x256 on 32x32x16 MFMAs
@@ -69,5 +72,4 @@ const GemmConfigDesc* generic_round_per_slice_config();              // gemm_gen
 const GemmConfigDesc* interleaved_config();                          // ladder/gemm_interleaved.hip
 const GemmConfigDesc* overlap_config();                              // ladder/gemm_overlap.hip
 const GemmConfigDesc* w4_config();                                   // ladder/gemm_w4.hip
-const GemmConfigDesc* w4a_config();                                  // ladder/gemm_w4a.hip: the same with its k loop in assembly
 #endif

@@ -1,22 +1,38 @@
-// The four-wavefront 256 x 256 x 64 kernel (see gemm_w4.hip for the shape and
-// why it is of interest on a power-limited part: a 128 x 128 wavefront tile
-// reads a third less LDS per flop than eight wavefronts of 128 x 64) with its
-// k loop written in assembly.  The C++ version spends a large part of every k
-// step on what the compiler adds around the MFMAs -- a wavefront that is alone
-// on its SIMD has nobody to hide that behind; here the loop body holds MFMAs,
-// LDS reads, copies and scalar pointer arithmetic only (gemm_w4a_loop.inc,
-// written by gen_w4a_loop.py, which also documents the schedule).
+// The long-k kernel: 256 x 256 C tile per workgroup, FOUR wavefronts (one per
+// SIMD), each owning a 128 x 128 block -- 8 x 8 accumulators of 16 x 16 = 256
+// registers, the whole AccVGPR file -- with its k loop written in assembly.
 //
-// Around the loop, in C++: the copy plan and fragment addresses (as in
-// gemm_w4.hip: same LDS image, same swizzles), the first two k steps' copies,
-// a k tail (K % 64 != 0) as one unpipelined step through registers after the
-// loop, and C + sum -> C.
+// Why this shape: under a dense MFMA load with random operands the part is
+// power-limited, so what counts is energy per flop, and a 128 x 128 wavefront
+// tile reads a third less LDS per flop than eight wavefronts of 128 x 64.  Why
+// assembly: a wavefront that is alone on its SIMD has nobody to hide the
+// compiler's address arithmetic, branches and waits behind (the C++ form of this
+// kernel, ladder/gemm_w4.hip, keeps the matrix pipe 43 % busy); here the loop
+// body holds MFMAs, LDS reads, copies and scalar pointer arithmetic only
+// (gemm_w4a_loop.inc, written by gen_w4a_loop.py, which documents the schedule).
+// Against the phase-alternating kernel it is level at four tiles of 128 k steps
+// per compute unit and 1-3 % ahead where k loops are longer; the selector takes
+// it there.
+//
+// The steps are those of the paper's recipe (Algorithm "Two-level tiled tensor
+// core Matmul"; the copies of later k tiles in flight while the current one is
+// multiplied, sections "Global Memory Load Latency Hiding" and "Completing
+// Latency Hiding").  C is moved once per tile (section "Generating WMMA Ops and
+// More"): in f32 mode, on tiles wholly inside C and with enough k steps, it is
+// read and added to the running sums during the first k steps of the loop
+// (a compute unit takes ~12 us to bring a tile of C in from HBM; behind the loop
+// its matrix units would idle meanwhile); otherwise behind the loop.
+//
+// Around the loop, in C++: the copy plan and fragment addresses (the LDS image
+// and swizzles of ladder/gemm_w4.hip), the first two k steps' copies, a k tail
+// (K % 64 != 0) as one unpipelined step through registers after the loop, and
+// the epilogue (+ C where it is not in the sums yet, + bias, ReLU, -> C).
 //
 // Requirements as for the other tuned kernels: A, B 16-byte aligned; lda, ldb,
 // K, N multiples of 8.  Rows >= M / columns >= N are fetched from clamped
 // addresses and never stored.
-#include "../gemm_device.h"
-#include "../../../include/gemm_f16.h"
+#include "gemm_device.h"
+#include "../../include/gemm_f16.h"
 #include "gemm_w4a_loop.inc"
 
 namespace {
@@ -190,6 +206,15 @@ __global__ __launch_bounds__(256) void gemm_w4a_kernel(const TiledParams p)
     }
 
     // ---- + C, -> C -------------------------------------------------------------------
+    // fused epilogue: this lane's 4 columns of the bias for each of its 8 block columns
+    float bias4[8][4];
+#pragma unroll
+    for (int fn = 0; fn < 8; fn++)
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            const int col = c_col0 + fn * 16 + c_lcol + e;
+            bias4[fn][e] = (p.bias && col < p.N) ? (float)reinterpret_cast<const CT*>(p.bias)[col] : 0.0f;
+        }
     auto c_ok = [&](int fm, int fn) -> bool {
         return !edge || ((c_row0 + fm * 16 + c_lrow < p.M) && (c_col0 + fn * 16 + c_lcol < p.N));
     };
@@ -217,7 +242,7 @@ __global__ __launch_bounds__(256) void gemm_w4a_kernel(const TiledParams p)
             for (int fn = 0; fn < 8; fn++) {
                 ctx4 v;
 #pragma unroll
-                for (int e = 0; e < 4; e++) v[e] = (CT)(acc[fm][fn][e] + (float)cin[r][fn][e]);   // f16: one rounding, to nearest even
+                for (int e = 0; e < 4; e++) v[e] = (CT)epilogue_value(acc[fm][fn][e] + (float)cin[r][fn][e], bias4[fn][e], p.relu);   // f16: one rounding, to nearest even
                 if (c_ok(fm, fn))
                     *reinterpret_cast<ctx4*>(rowp + c_voff + fn * 16 * sizeof(CT)) = v;
             }
@@ -232,7 +257,7 @@ __global__ __launch_bounds__(256) void gemm_w4a_kernel(const TiledParams p)
             for (int fn = 0; fn < 8; fn++) {
                 ctx4 v;
 #pragma unroll
-                for (int e = 0; e < 4; e++) v[e] = (CT)acc[fm][fn][e];
+                for (int e = 0; e < 4; e++) v[e] = (CT)epilogue_value(acc[fm][fn][e], bias4[fn][e], p.relu);
                 *reinterpret_cast<ctx4*>(rowp + c_voff + fn * 16 * sizeof(CT)) = v;
             }
         }
@@ -258,9 +283,7 @@ int launch_w4a(const GemmArgs& a)
 {
     const int64_t g = grid_w4a(a.M, a.N);
     if (g < 0) return GEMM_F16_ERR_SIZE;
-    if (a.bias || a.relu) return GEMM_F16_ERR_CONFIG;      // this comparison kernel has no fused epilogue
-    TiledParams p = make_tiled_params(a, WBM, WBN, 8);     // an XCD's 32 concurrent tiles form an 8 x 4 block of C
-    p.bias = nullptr; p.relu = 0;
+    const TiledParams p = make_tiled_params(a, WBM, WBN, 8);   // an XCD's 32 concurrent tiles form an 8 x 4 block of C
     if (a.c_is_f16)
         hipLaunchKernelGGL(gemm_w4a_kernel<half_t>, dim3((unsigned)g), dim3(256), 0, a.stream, p);
     else
@@ -273,4 +296,4 @@ const GemmConfigDesc kW4a = {
 
 }  // namespace
 
-const GemmConfigDesc* w4a_config() { return &kW4a; }
+const GemmConfigDesc* long_k_config() { return &kW4a; }

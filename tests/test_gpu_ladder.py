@@ -18,7 +18,7 @@ from gpu_util import run_gemm, assert_close, config_id       # noqa: E402
 
 CDT = {"f32": np.float32, "f16": np.float16}
 ROWS = ["t128x128x64_w2x2", "t256x256x64_w2x4", "t256x256x64_w2x4_noswz", "pp256x256x64_w2x4",
-        "pp256x256x64_w2x4_mi16_noxcd", "w4_256x256x64", "w4a_256x256x64", "il256x256x64_w2x4_mi16", "generic64x64x32_c_in_loop",
+        "pp256x256x64_w2x4_mi16_noxcd", "w4_256x256x64", "il256x256x64_w2x4_mi16", "generic64x64x32_c_in_loop",
         "generic64x64x32_f16_round_per_slice"]
 SHAPES = [(64, 64, 64), (300, 264, 200), (520, 776, 136), (257, 8, 8), (1, 520, 72), (130, 136, 1000),
           (513, 264, 64), (256, 256, 8), (1100, 1296, 448)]
@@ -117,44 +117,8 @@ def test_f16_running_sum_rounded_every_16_k_matches_the_literal_reading(oracle_m
     print(f"per-slice rounding on the GPU: worst |C - C_ref| / S = {worst_ref:.2e}, worst |C - literal oracle| / S = {worst_lit:.2e}")
 
 
-def test_assembly_k_loop_at_every_exit_of_its_six_step_body(oracle_mod):
-    """The four-wavefront kernel's assembly k loop is unrolled six k steps deep and can leave
-    after any of them: 1 to 14 full k steps (two trips and more), with and without a k tail,
-    on several tiles with ragged edges; integers, so every bit counts."""
-    binding.force_config(config_id("w4a_256x256x64"))
-    for steps in range(1, 15):
-        for tail in (0, 24):
-            M, N, K = 300, 520, 64 * steps + tail
-            A, B, _ = wl.make_inputs(M, N, K, "int2", "zeros", seed=900 + steps)
-            C0 = np.random.default_rng(steps).integers(-4, 5, size=(M, N)).astype(np.float32)
-            got = run_gemm(A, B, C0, "f32")
-            Cref, _ = oracle_mod.gemm_f16(A, B, C0)
-            assert np.array_equal(got, oracle_mod.round_to_f32(Cref)), f"K = {K}"
-
-
-def test_c_read_inside_the_assembly_loop(oracle_mod):
-    """In f32 mode, on tiles that lie wholly inside C and with enough full k steps (a few dozen),
-    the four-wavefront kernel reads C during its first k steps and adds it to the running sums
-    there.  Shapes with interior and edge tiles side by side, 40 to 51 full k steps, with and
-    without a k tail, a C pitch that is not N: integers bit for bit, random data to tolerance
-    (both modes: f16 takes the path that adds C behind the loop)."""
-    binding.force_config(config_id("w4a_256x256x64"))
-    for idx, (M, N, K) in enumerate([(256, 256, 2560), (512, 768, 2624), (600, 520, 2688 + 24), (256, 512, 3264), (768, 300, 2816)]):
-        A, B, _ = wl.make_inputs(M, N, K, "int2", "zeros", seed=950 + idx)
-        C0 = np.random.default_rng(idx).integers(-4, 5, size=(M, N)).astype(np.float32)
-        got = run_gemm(A, B, C0, "f32", ldc=N + 8 * idx)
-        Cref, _ = oracle_mod.gemm_f16(A, B, C0)
-        assert np.array_equal(got, oracle_mod.round_to_f32(Cref)), f"ints {(M, N, K)}"
-        for mode in ("f32", "f16"):
-            A, B, C0 = wl.make_inputs(M, N, K, "uniform", "uniform", seed=960 + idx, c_dtype=CDT[mode])
-            got = run_gemm(A, B, C0, mode)
-            Cref, S = oracle_mod.gemm_f16(A, B, C0)
-            assert_close(got, Cref, S, C0, mode, what=f"w4a, C in the loop {(M, N, K)} {mode}")
-
-
-@pytest.mark.parametrize("name", ["w4_256x256x64", "w4a_256x256x64"])
-def test_the_four_wavefront_kernels_have_no_fused_epilogue(name):
-    binding.force_config(config_id(name))
+def test_the_four_wavefront_ladder_kernel_has_no_fused_epilogue():
+    binding.force_config(config_id("w4_256x256x64"))
     dev = torch.device("cuda:0")
     A = torch.zeros(256, 64, dtype=torch.float16, device=dev)
     B = torch.zeros(64, 256, dtype=torch.float16, device=dev)

@@ -1,0 +1,78 @@
+"""GPU parity of what is particular to the long-k kernel (four wavefronts of 128 x 128, k loop in
+assembly): leaving the loop at each of its exits, C read inside the loop, and where the
+selector takes it.  The tests over all configurations (test_gpu_parity.py,
+test_gpu_fused_epilogue.py) cover it like every other product kernel."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+if not torch.cuda.is_available():
+    pytest.skip("no GPU", allow_module_level=True)
+
+from paper_2108_13191_amd import binding, workloads as wl   # noqa: E402
+from gpu_util import run_gemm, assert_close, config_id       # noqa: E402
+
+CDT = {"f32": np.float32, "f16": np.float16}
+NAME = "w4a_256x256x64"
+
+
+@pytest.fixture(autouse=True)
+def _unforce():
+    binding.force_config(-1)
+    yield
+    binding.force_config(-1)
+
+
+def test_assembly_k_loop_at_every_exit_of_its_six_step_body(oracle_mod):
+    """The assembly k loop is unrolled six k steps deep and can leave
+    after any of them: 1 to 14 full k steps (two trips and more), with and without a k tail,
+    on several tiles with ragged edges; integers, so every bit counts."""
+    binding.force_config(config_id(NAME))
+    for steps in range(1, 15):
+        for tail in (0, 24):
+            M, N, K = 300, 520, 64 * steps + tail
+            A, B, _ = wl.make_inputs(M, N, K, "int2", "zeros", seed=900 + steps)
+            C0 = np.random.default_rng(steps).integers(-4, 5, size=(M, N)).astype(np.float32)
+            got = run_gemm(A, B, C0, "f32")
+            Cref, _ = oracle_mod.gemm_f16(A, B, C0)
+            assert np.array_equal(got, oracle_mod.round_to_f32(Cref)), f"K = {K}"
+
+
+def test_c_read_inside_the_assembly_loop(oracle_mod):
+    """In f32 mode, on tiles that lie wholly inside C and with enough full k steps (a few dozen),
+    the four-wavefront kernel reads C during its first k steps and adds it to the running sums
+    there.  Shapes with interior and edge tiles side by side, 40 to 51 full k steps, with and
+    without a k tail, a C pitch that is not N: integers bit for bit, random data to tolerance
+    (both modes: f16 takes the path that adds C behind the loop)."""
+    binding.force_config(config_id(NAME))
+    for idx, (M, N, K) in enumerate([(256, 256, 2560), (512, 768, 2624), (600, 520, 2688 + 24), (256, 512, 3264), (768, 300, 2816)]):
+        A, B, _ = wl.make_inputs(M, N, K, "int2", "zeros", seed=950 + idx)
+        C0 = np.random.default_rng(idx).integers(-4, 5, size=(M, N)).astype(np.float32)
+        got = run_gemm(A, B, C0, "f32", ldc=N + 8 * idx)
+        Cref, _ = oracle_mod.gemm_f16(A, B, C0)
+        assert np.array_equal(got, oracle_mod.round_to_f32(Cref)), f"ints {(M, N, K)}"
+        for mode in ("f32", "f16"):
+            A, B, C0 = wl.make_inputs(M, N, K, "uniform", "uniform", seed=960 + idx, c_dtype=CDT[mode])
+            got = run_gemm(A, B, C0, mode)
+            Cref, S = oracle_mod.gemm_f16(A, B, C0)
+            assert_close(got, Cref, S, C0, mode, what=f"w4a, C in the loop {(M, N, K)} {mode}")
+
+
+def test_selected_for_long_k_loops_and_right_there(oracle_mod):
+    """K >= 12288 on whole 256 x 256 tiles (and K >= 8192 at no more than one tile per compute
+    unit) goes to this kernel under automatic selection; sampled rows of such a problem
+    against the oracle, both modes."""
+    M, N, K = 4096, 4096, 8192
+    for mode in ("f32", "f16"):
+        q = binding.query_config(mode == "f16", M, N, K, 16, K, 16, N, 16, N)
+        assert q["name"] == NAME, q
+        A, B, C0 = wl.make_inputs(M, N, K, "normal_rsqrtk", "uniform", seed=31, c_dtype=CDT[mode])
+        got = run_gemm(A, B, C0, mode)
+        rows = np.array([0, 1, 127, 128, 255, 256, 300, 511, 2047, 2048, 4095])
+        Cref, S = oracle_mod.gemm_f16(A, B, C0, rows=rows)
+        assert_close(got[rows], Cref, S, C0[rows], mode, what=f"long k, auto {mode}")
+    assert binding.query_config(0, 8192, 8192, 8192, 16, 8192, 16, 8192, 16, 8192)["name"].endswith("_chain")
+    for n in (12288, 16384):
+        assert binding.query_config(0, n, n, n, 16, n, 16, n, 16, n)["name"] == NAME

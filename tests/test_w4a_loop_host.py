@@ -1,5 +1,5 @@
-"""CPU checks of the generated assembly k loop of the four-wavefront ladder kernel
-(csrc/ladder/gen_w4a_loop.py -> gemm_w4a_loop.inc): the committed file is what the generator
+"""CPU checks of the generated assembly k loop of the long-k kernel
+(csrc/gen_w4a_loop.py -> gemm_w4a_loop.inc): the committed file is what the generator
 writes, and an emulation of the loop's scalar side (pointer arithmetic with carries, selects,
 branches) for 1..40 k steps shows that every copy fetches a k step below KT from the right
 address into the right LDS buffer, that every fragment read touches the buffer that holds its
@@ -14,7 +14,7 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-GEN = os.path.join(ROOT, "paper_2108_13191_amd", "csrc", "ladder", "gen_w4a_loop.py")
+GEN = os.path.join(ROOT, "paper_2108_13191_amd", "csrc", "gen_w4a_loop.py")
 
 
 def _generator():
