@@ -189,17 +189,24 @@ int chained_if_it_pays(int id, int64_t rows, int64_t N, int64_t K)
     return c->grid(rows, N) < config(ID_PP256)->grid(rows, N) ? id_chained() : id;
 }
 
-// Long k loops take the four-wavefront kernel.  Measured against the chained 256 x 256 form,
-// both alternating in one process at the steady state (f32 / f16 mode): K = 16384: 16384^3
-// +3.5 ... +4.4 / +2.5 %, 8192^2 +1.3 ... +4 / +2 ... +4 %, 6144 x 8192 +2 / +2 %; K = 12288:
-// 12288^3 +1 ... +5 / +2 %, 16384^2 +1 ... +1.7 / +1 %, 8192 x 16384 0 %, 8192^2 -1 / 0 %;
-// K = 8192: 4096^2 (one tile per compute unit) +4.4 / +0.5 %, 4096 x 8192 +2 / 0 %, 8192^2
-// -0.5 ... -1 %, 12288^2 -1 ... -2 %, 16384^2 0 %; K = 4096: -1 ... -10 %.
-int long_k_if_it_pays(int id, int64_t rows, int64_t N, int64_t K)
+// Long k loops take the four-wavefront kernel, and so do f32 problems of at most one 256 x 256
+// tile per compute unit: there nothing else hides the read of C, which that kernel does inside
+// its k loop (from 36 k steps on).  Measured against the plain / chained 256 x 256 form, all
+// alternating in one process at the steady state (f32 / f16 mode): K = 16384: 16384^3 +3.5 ...
+// +4.4 / +2.5 %, 8192^2 +1.3 ... +4 / +2 ... +4 %, 6144 x 8192 +2 / +2 %; K = 12288: 12288^3
+// +1 ... +5 / +2 %, 16384^2 +1 ... +1.7 / +1 %, 8192 x 16384 0 %, 8192^2 -1 / 0 %; K = 8192:
+// 4096^2 (one tile per compute unit) +5 / +0.5 %, 4096 x 8192 (two) +2 / 0 %, 8192^2 -0.5 ... -1 %,
+// 12288^2 -1 ... -2 %, 16384^2 0 %; one tile per compute unit, K = 6144 / 4096 / 3072 / 2304: +6.5,
+// +8, +8, +10 % in f32 mode (3840 x 4096 x 4096, 240 tiles: +5 %), -2 ... -9 % in f16 mode (C read
+// behind the loop); K = 2048 (no C in the loop): -10 %; two tiles per compute unit, K = 4096 /
+// 6144: -2 / 0 % (f16 -5 / -2 %).
+int long_k_if_it_pays(int id, int c_is_f16, int64_t rows, int64_t N, int64_t K)
 {
     if (id != ID_PP256 && id != ID_CHAIN) return id;
-    const int64_t tiles = config(ID_PP256)->grid(rows, N);
-    return (K >= 12288 || (K >= 8192 && tiles <= 2 * (int64_t)chip().cus)) ? ID_LONG_K : id;
+    const int64_t tiles = config(ID_PP256)->grid(rows, N), cus = chip().cus;
+    const bool whole_tiles = rows % 256 == 0 && N % 256 == 0;      // an edge tile reads C behind the loop (4000^3: -9 %)
+    const bool pays = K >= 12288 || (K >= 8192 && tiles <= 2 * cus) || (!c_is_f16 && K >= 2304 && tiles <= cus && whole_tiles);
+    return pays ? ID_LONG_K : id;
 }
 
 Plan select_plan_unchained(int c_is_f16, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, int64_t ldc)
@@ -236,8 +243,8 @@ Plan select_plan(int c_is_f16, int64_t M, int64_t N, int64_t K, const void* A, i
 {
     Plan pl = select_plan_unchained(c_is_f16, M, N, K, A, lda, B, ldb, ldc);
     if (g_forced >= 0 && g_forced < num_configs()) return pl;        // a forced configuration runs as it is
-    pl.id = long_k_if_it_pays(chained_if_it_pays(pl.id, pl.rows1, N, K), pl.rows1, N, K);
-    if (pl.id2 >= 0) pl.id2 = long_k_if_it_pays(chained_if_it_pays(pl.id2, M - pl.rows1, N, K), M - pl.rows1, N, K);
+    pl.id = long_k_if_it_pays(chained_if_it_pays(pl.id, pl.rows1, N, K), c_is_f16, pl.rows1, N, K);
+    if (pl.id2 >= 0) pl.id2 = long_k_if_it_pays(chained_if_it_pays(pl.id2, M - pl.rows1, N, K), c_is_f16, M - pl.rows1, N, K);
     return pl;
 }
 
