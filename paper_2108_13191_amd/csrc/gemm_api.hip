@@ -197,15 +197,16 @@ int chained_if_it_pays(int id, int64_t rows, int64_t N, int64_t K)
 // +1 ... +5 / +2 %, 16384^2 +1 ... +1.7 / +1 %, 8192 x 16384 0 %, 8192^2 -1 / 0 %; K = 8192:
 // 4096^2 (one tile per compute unit) +5 / +0.5 %, 4096 x 8192 (two) +2 / 0 %, 8192^2 -0.5 ... -1 %,
 // 12288^2 -1 ... -2 %, 16384^2 0 %; one tile per compute unit, K = 6144 / 4096 / 3072 / 2304: +6.5,
-// +8, +8, +10 % in f32 mode (3840 x 4096 x 4096, 240 tiles: +5 %), -2 ... -9 % in f16 mode (C read
-// behind the loop); K = 2048 (no C in the loop): -10 %; two tiles per compute unit, K = 4096 /
-// 6144: -2 / 0 % (f16 -5 / -2 %).
+// +8, +8, +10 % in f32 mode (3840 x 4096 x 4096, 240 tiles: +5 %; ragged 4000 x 4000 x 4096 +2.5 %,
+// 3900 x 4000 x 3072 +2 %: edge tiles read and store C through range-checked buffer accesses),
+// -2 ... -9 % in f16 mode (C read behind the loop); K = 2048 (no C in the loop): -10 %; two tiles
+// per compute unit, K = 4096 / 6144: -2 / 0 % (f16 -5 / -2 %).
 int long_k_if_it_pays(int id, int c_is_f16, int64_t rows, int64_t N, int64_t K)
 {
     if (id != ID_PP256 && id != ID_CHAIN) return id;
     const int64_t tiles = config(ID_PP256)->grid(rows, N), cus = chip().cus;
-    const bool whole_tiles = rows % 256 == 0 && N % 256 == 0;      // an edge tile reads C behind the loop (4000^3: -9 %)
-    const bool pays = K >= 12288 || (K >= 8192 && tiles <= 2 * cus) || (!c_is_f16 && K >= 2304 && tiles <= cus && whole_tiles);
+    // (a k tail is an unpipelined step behind that kernel's loop: 4000^3 +1 %, left where it was)
+    const bool pays = K >= 12288 || (K >= 8192 && tiles <= 2 * cus) || (!c_is_f16 && K >= 2304 && K % 64 == 0 && tiles <= cus);
     return pays ? ID_LONG_K : id;
 }
 

@@ -18,10 +18,12 @@
 // core Matmul"; the copies of later k tiles in flight while the current one is
 // multiplied, sections "Global Memory Load Latency Hiding" and "Completing
 // Latency Hiding").  C is moved once per tile (section "Generating WMMA Ops and
-// More"): in f32 mode, on tiles wholly inside C and with enough k steps, it is
-// read and added to the running sums during the first k steps of the loop
-// (a compute unit takes ~12 us to bring a tile of C in from HBM; behind the loop
-// its matrix units would idle meanwhile); otherwise behind the loop.
+// More"): in f32 mode, with enough k steps, it is read and added to the running
+// sums during the first k steps of the loop (a compute unit takes ~12 us to
+// bring a tile of C in from HBM; behind the loop its matrix units would idle
+// meanwhile) and stored behind it, both through a range-checked buffer view of
+// the wavefront's part of C, so that edge tiles take the same straight-line
+// code; otherwise it is read, added and stored behind the loop.
 //
 // Around the loop, in C++: the copy plan and fragment addresses (the LDS image
 // and swizzles of ladder/gemm_w4.hip), the first two k steps' copies, a k tail
@@ -31,6 +33,7 @@
 // Requirements as for the other tuned kernels: A, B 16-byte aligned; lda, ldb,
 // K, N multiples of 8.  Rows >= M / columns >= N are fetched from clamped
 // addresses and never stored.
+#include <type_traits>
 #include "gemm_device.h"
 #include "../../include/gemm_f16.h"
 #include "gemm_w4a_loop.inc"
@@ -130,9 +133,20 @@ __global__ __launch_bounds__(256) void gemm_w4a_kernel(const TiledParams p)
     const int c_lrow = lane & 15, c_lcol = 4 * (lane >> 4);
     const uint32_t c_voff = ((uint32_t)c_lrow * (uint32_t)p.ldc + (uint32_t)c_lcol) * (uint32_t)sizeof(CT);
     const int c_row0 = m0 + wm_base, c_col0 = n0 + wn_base;
-    // C is read and added inside the loop where every load is a full, unmasked f32 access and
-    // the loop is long enough; otherwise behind it
-    const bool c_in_loop = sizeof(CT) == 4 && !edge && kt_full >= W4A_C_STEPS;
+    // C is read and added inside the loop in f32 mode where the loop is long enough; otherwise
+    // behind it
+    const bool c_in_loop = sizeof(CT) == 4 && kt_full >= W4A_C_STEPS;
+    // The loads inside the loop are range-checked buffer loads on this wavefront's part of C:
+    // base = its first element, c_bytes = distance to the end of C's last element (0 if the
+    // block lies outside C; offsets inside a 128-row block stay below 2^31).  A row beyond C's
+    // last is out of range by that; a lane whose 4 columns of block column fn lie beyond C's
+    // last gets an offset that is out of range whatever the row.  Out of range = no access, 0.
+    uint32_t c_voff_fn[8];
+#pragma unroll
+    for (int fn = 0; fn < 8; fn++) c_voff_fn[fn] = (c_col0 + fn * 16 + c_lcol < p.N) ? c_voff : 0x80000000u;
+    const int64_t c_span = (c_row0 < p.M && c_col0 < p.N)
+                               ? ((int64_t)(p.M - 1 - c_row0) * p.ldc + (p.N - c_col0)) * (int64_t)sizeof(CT) : 0;
+    const uint32_t c_bytes = __builtin_amdgcn_readfirstlane((uint32_t)(c_span < 0x7fffffff ? c_span : 0x7fffffff));
 
     floatx4 acc[8][8];
     if (kt_full > 0) {
@@ -159,7 +173,7 @@ __global__ __launch_bounds__(256) void gemm_w4a_kernel(const TiledParams p)
         const uint32_t a_ptr_lo = __builtin_amdgcn_readfirstlane((uint32_t)a_ptr), a_ptr_hi = __builtin_amdgcn_readfirstlane((uint32_t)(a_ptr >> 32));
         const uint32_t b_ptr_lo = __builtin_amdgcn_readfirstlane((uint32_t)b_ptr), b_ptr_hi = __builtin_amdgcn_readfirstlane((uint32_t)(b_ptr >> 32));
         const uint64_t c_wave = (uint64_t)(uintptr_t)(Cbase + (int64_t)c_row0 * p.ldc + c_col0);
-        const uint32_t c_lo = __builtin_amdgcn_readfirstlane((uint32_t)c_wave), c_hi = __builtin_amdgcn_readfirstlane((uint32_t)(c_wave >> 32));
+        const uint32_t c_lo = __builtin_amdgcn_readfirstlane((uint32_t)c_wave), c_hi = __builtin_amdgcn_readfirstlane((uint32_t)(c_wave >> 32) & 0xffffu);
         const uint32_t c_rowstep = 16u * (uint32_t)p.ldc * (uint32_t)sizeof(CT);    // bytes from one row of blocks to the next (ldc <= 2^22)
         if (c_in_loop)
             asm volatile(W4A_LOOP_C_ASM : W4A_LOOP_OUTPUTS(acc) : W4A_LOOP_INPUTS : W4A_LOOP_CLOBBERS);
@@ -249,18 +263,23 @@ __global__ __launch_bounds__(256) void gemm_w4a_kernel(const TiledParams p)
         }
     };
     auto fence = [&]() { __builtin_amdgcn_sched_barrier(0); };
-    if (c_in_loop) {                 // never an edge tile: every store is inside C
+    if (c_in_loop) {
+        // C is in the sums already: only stores, through the same range-checked view of C as
+        // the loads in the loop -- a store to a row or column beyond C's last is dropped by the
+        // check, so that edge tiles need no masks either
+        const __amdgpu_buffer_rsrc_t c_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            (void*)(Cbase + (int64_t)c_row0 * p.ldc + c_col0), 0, c_bytes, 0x20000);
+        const uint32_t c_rowstep = 16u * (uint32_t)p.ldc * (uint32_t)sizeof(CT);
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #pragma unroll
-        for (int fm = 0; fm < 8; fm++) {
-            char* rowp = reinterpret_cast<char*>(Cbase + (int64_t)(c_row0 + fm * 16) * p.ldc + c_col0);
+        for (int fm = 0; fm < 8; fm++)
 #pragma unroll
             for (int fn = 0; fn < 8; fn++) {
-                ctx4 v;
+                floatx4 v;
 #pragma unroll
-                for (int e = 0; e < 4; e++) v[e] = (CT)epilogue_value(acc[fm][fn][e], bias4[fn][e], p.relu);
-                *reinterpret_cast<ctx4*>(rowp + c_voff + fn * 16 * sizeof(CT)) = v;
+                for (int e = 0; e < 4; e++) v[e] = epilogue_value(acc[fm][fn][e], bias4[fn][e], p.relu);
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), c_rsrc, c_voff_fn[fn] + fn * 64, fm * c_rowstep, 0);
             }
-        }
         return;
     }
     ctx4 c_q0[2][8], c_q1[2][8], c_q2[2][8];

@@ -36,7 +36,10 @@ the matrix units would idle if it were done behind the loop.  Its first
 C_STEPS k steps are a straight-line section in which, besides the schedule above,
 
     after MFMA 63 of slice 1 of step j        C_PER_STEP 16 x 16 blocks of C are loaded (one 16-byte
-                                              load per lane and block) into one of three register sets
+                                              load per lane and block) into one of three register sets;
+                                              buffer loads, whose range check returns 0 for rows beyond
+                                              C's last (the caller puts lanes whose columns lie beyond
+                                              C's last out of range through their offset register)
     in slice 1 of step j + 2 (they have       those blocks are added to their accumulators: read the
     landed: the wait in the middle of that    AccVGPR, add, write it back, three instructions in the
     step leaves only younger loads out)       shadow of an MFMA, never next to an MFMA of that block
@@ -61,8 +64,9 @@ C_STEPS = ((C_LOAD_STEPS + 2 + 5) // 6) * 6   # length of the section: the last 
 S_J, S_J2 = "s64", "s65"
 S_ASRC, S_BSRC = "s[66:67]", "s[68:69]"          # sources of this step's copies
 S_APTR, S_BPTR = ("s70", "s71"), ("s72", "s73")  # running: k step j + 2
-S_CPTR = ("s74", "s75")                          # running: this wavefront's C, row of blocks fm
-SCALAR_CLOBBERS = [f"s{i}" for i in range(64, 76)]
+S_CSOFF = "s74"                                  # running: byte offset of the row of blocks fm in this wavefront's C
+S_CRSRC = "s[76:79]"                             # buffer descriptor of this wavefront's part of C
+SCALAR_CLOBBERS = [f"s{i}" for i in range(64, 80)]
 V_CTMP = 128                                     # 3 sets x C_PER_STEP blocks x 4 registers of C
 V_T = V_CTMP + 3 * C_PER_STEP * 4                # 3 scratch registers for the adds
 V_CLOBBERED = V_T + 3
@@ -179,9 +183,9 @@ def k_step(ph, exits=True, loads=(), adds=(), loads_before=0):
         if i == 60:
             out += [f"s_add_u32 {S_J}, {S_J}, 1"]
     for b, reg in loads:
-        out.append(f"global_load_dwordx4 v[{reg}:{reg + 3}], %[c_voff], s[74:75] offset:{(b & 7) * 64}")
+        out.append(f"buffer_load_dwordx4 v[{reg}:{reg + 3}], %[c_voff{b & 7}], {S_CRSRC}, {S_CSOFF} offen offset:{(b & 7) * 64}")
         if b & 7 == 7:
-            out += [f"s_add_u32 {S_CPTR[0]}, {S_CPTR[0]}, %[c_rowstep]", f"s_addc_u32 {S_CPTR[1]}, {S_CPTR[1]}, 0"]
+            out.append(f"s_add_u32 {S_CSOFF}, {S_CSOFF}, %[c_rowstep]")
     out.append("s_waitcnt lgkmcnt(0)")
     if exits:
         out.append(f"s_cmp_lt_u32 {S_J}, %[kt]")
@@ -197,7 +201,9 @@ def head(with_c):
             f"s_mov_b32 {S_APTR[0]}, %[a_ptr_lo]", f"s_mov_b32 {S_APTR[1]}, %[a_ptr_hi]",
             f"s_mov_b32 {S_BPTR[0]}, %[b_ptr_lo]", f"s_mov_b32 {S_BPTR[1]}, %[b_ptr_hi]"]
     if with_c:
-        out += [f"s_mov_b32 {S_CPTR[0]}, %[c_lo]", f"s_mov_b32 {S_CPTR[1]}, %[c_hi]"]
+        # raw buffer (stride 0): base, number of bytes that may be read from it, 32-bit data format
+        out += ["s_mov_b32 s76, %[c_lo]", "s_mov_b32 s77, %[c_hi]", "s_mov_b32 s78, %[c_bytes]", "s_mov_b32 s79, 0x20000",
+                f"s_mov_b32 {S_CSOFF}, 0"]
     for r in range(24):
         out.append(read(0, 0, 0, r))
     out.append("s_waitcnt lgkmcnt(0)")
@@ -261,11 +267,11 @@ def render():
     vin += [f'[b_rdh{f}] "v"(b_rd[{f}] + {2 * B_BUF}u)' for f in range(8)]
     vin += [f'[a_off{t}] "v"(a_off[{t}])' for t in range(8)]
     vin += [f'[b_off{t}] "v"(b_off[{t}])' for t in range(8)]
-    vin += ['[c_voff] "v"(c_voff)']
+    vin += [f'[c_voff{f}] "v"(c_voff_fn[{f}])' for f in range(8)]
     sin = ['[lds_wave] "s"(lds_wave)', '[kt] "s"(kt_full)', '[b_step] "s"(b_step)',
            '[a_base_lo] "s"(a_base_lo)', '[a_base_hi] "s"(a_base_hi)', '[b_base_lo] "s"(b_base_lo)', '[b_base_hi] "s"(b_base_hi)',
            '[a_ptr_lo] "s"(a_ptr_lo)', '[a_ptr_hi] "s"(a_ptr_hi)', '[b_ptr_lo] "s"(b_ptr_lo)', '[b_ptr_hi] "s"(b_ptr_hi)',
-           '[c_lo] "s"(c_lo)', '[c_hi] "s"(c_hi)', '[c_rowstep] "s"(c_rowstep)']
+           '[c_lo] "s"(c_lo)', '[c_hi] "s"(c_hi)', '[c_bytes] "s"(c_bytes)', '[c_rowstep] "s"(c_rowstep)']
     text.append("#define W4A_LOOP_INPUTS \\")
     allin = vin + sin
     rows = [", ".join(allin[i:i + 4]) for i in range(0, len(allin), 4)]

@@ -47,7 +47,7 @@ def test_c_read_inside_the_assembly_loop(oracle_mod):
     without a k tail, a C pitch that is not N: integers bit for bit, random data to tolerance
     (both modes: f16 takes the path that adds C behind the loop)."""
     binding.force_config(config_id(NAME))
-    for idx, (M, N, K) in enumerate([(256, 256, 2560), (512, 768, 2624), (600, 520, 2688 + 24), (256, 512, 3264), (768, 300, 2816)]):
+    for idx, (M, N, K) in enumerate([(256, 256, 2560), (512, 768, 2624), (600, 520, 2688 + 24), (256, 512, 3264), (768, 300, 2816), (416, 672, 2560)]):
         A, B, _ = wl.make_inputs(M, N, K, "int2", "zeros", seed=950 + idx)
         C0 = np.random.default_rng(idx).integers(-4, 5, size=(M, N)).astype(np.float32)
         got = run_gemm(A, B, C0, "f32", ldc=N + 8 * idx)

@@ -33,8 +33,9 @@ def test_committed_include_is_what_the_generator_writes():
 A_BASE = 0x100000000 - 4096        # the running A pointer crosses a 32-bit carry
 B_BASE = 0x7000000000
 B_STEP = 64 * 8192 * 2
-C_BASE = 0x300000000 - 3 * 16 * 8192 * 4 - 64      # the C row pointer crosses a 32-bit carry
+C_BASE = 0x300000000 - 3 * 16 * 8192 * 4 - 64
 C_ROWSTEP = 16 * 8192 * 4
+C_BYTES = 0x12345678
 LDS_WAVE = 3072
 
 
@@ -46,7 +47,7 @@ def _run(lines, kt):
          "%[b_base_lo]": B_BASE & 0xffffffff, "%[b_base_hi]": B_BASE >> 32}
     ap, bp = A_BASE + 2 * 128, B_BASE + 2 * B_STEP
     S.update({"%[a_ptr_lo]": ap & 0xffffffff, "%[a_ptr_hi]": ap >> 32, "%[b_ptr_lo]": bp & 0xffffffff, "%[b_ptr_hi]": bp >> 32})
-    S.update({"%[c_lo]": C_BASE & 0xffffffff, "%[c_hi]": C_BASE >> 32, "%[c_rowstep]": C_ROWSTEP})
+    S.update({"%[c_lo]": C_BASE & 0xffffffff, "%[c_hi]": C_BASE >> 32, "%[c_rowstep]": C_ROWSTEP, "%[c_bytes]": C_BYTES})
 
     def val(x):
         return S[x] if x in S else int(x)
@@ -63,7 +64,7 @@ def _run(lines, kt):
         op, _, rest = ln.partition(" ")
         a = [x.strip() for x in rest.split(",")]
         if op == "s_mov_b32":
-            S[a[0]] = val(a[1])
+            S[a[0]] = int(a[1], 16) if a[1].startswith("0x") else val(a[1])
         elif op == "s_add_u32":
             r = val(a[1]) + val(a[2]); S[a[0]] = r & 0xffffffff; scc = r >> 32
         elif op == "s_addc_u32":
@@ -80,11 +81,16 @@ def _run(lines, kt):
             m = re.match(r"s\[(\d+):(\d+)\]", a[1])
             src = S[f"s{m.group(1)}"] | (S[f"s{m.group(2)}"] << 32)
             trace.append((t, "copy", a[0], src, S["m0"], nmfma))
-        elif op == "global_load_dwordx4":
+        elif op == "buffer_load_dwordx4":
+            # v[..], per-lane offset of block column fn, descriptor s[76:79] (base in s76, s77), scalar offset, immediate
             m = re.match(r"v\[(\d+):(\d+)\]", a[0])
-            m2 = re.match(r"s\[(\d+):(\d+)\] offset:(\d+)", a[2])
-            assert a[1] == "%[c_voff]" and int(m.group(2)) == int(m.group(1)) + 3
-            src = (S[f"s{m2.group(1)}"] | (S[f"s{m2.group(2)}"] << 32)) + int(m2.group(3))
+            m2 = re.match(r"(s\d+) offen offset:(\d+)", a[3])
+            assert a[2] == "s[76:79]" and int(m.group(2)) == int(m.group(1)) + 3
+            assert S["s78"] == C_BYTES and S["s79"] == 0x20000 and S["s77"] < 0x10000
+            assert a[1] == f"%[c_voff{int(m2.group(2)) // 64}]", "the offset register of another block column"
+            off = S[m2.group(1)] + int(m2.group(2))
+            assert off < 2 ** 31
+            src = (S["s76"] | (S["s77"] << 32)) + off
             trace.append((t, "cload", int(m.group(1)), src, nmfma))
         elif op == "v_accvgpr_read_b32":
             trace.append((t, "accread", a[0], int(a[1][1:]), nmfma))
