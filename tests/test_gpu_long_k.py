@@ -41,11 +41,14 @@ def test_assembly_k_loop_at_every_exit_of_its_six_step_body(oracle_mod):
 
 
 def test_c_read_inside_the_assembly_loop(oracle_mod):
-    """In f32 mode, on tiles that lie wholly inside C and with enough full k steps (a few dozen),
-    the four-wavefront kernel reads C during its first k steps and adds it to the running sums
-    there.  Shapes with interior and edge tiles side by side, 40 to 51 full k steps, with and
-    without a k tail, a C pitch that is not N: integers bit for bit, random data to tolerance
-    (both modes: f16 takes the path that adds C behind the loop)."""
+    """In f32 mode, with enough full k steps (a few dozen), the long-k kernel reads C during its
+    first k steps and adds it to the running sums there, through range-checked buffer loads, and
+    stores through the same view of C.  Shapes with interior and edge tiles side by side, edge
+    tiles whose wavefront blocks lie inside, across and outside C's border (160, 88, 44 and 8 of
+    256 rows or columns inside C), 40 to 51 full k steps, with and without a k tail, a C pitch
+    that is not N: integers bit for bit (and nothing outside C written: the helper compares the
+    canaries around it), random data to tolerance (both modes: f16 takes the path that adds C
+    behind the loop)."""
     binding.force_config(config_id(NAME))
     for idx, (M, N, K) in enumerate([(256, 256, 2560), (512, 768, 2624), (600, 520, 2688 + 24), (256, 512, 3264), (768, 300, 2816), (416, 672, 2560)]):
         A, B, _ = wl.make_inputs(M, N, K, "int2", "zeros", seed=950 + idx)
