@@ -62,6 +62,9 @@ const GemmConfigDesc* pingpong16_staggered_config();                  // 256x256
 // gemm_w4a.hip
 const GemmConfigDesc* long_k_config();                                // 256x256, four wavefronts of 128x128, k loop in assembly
 
+// gemm_w4a128.hip
+const GemmConfigDesc* small_tile_asm_config();                        // 128x128, four wavefronts of 64x64, k loop in assembly
+
 #ifdef GEMM_F16_LADDER
 // Comparison kernels and ablation rows: built into libgemm_f16_ladder.so only, never selected.
 const GemmConfigDesc* pingpong_config();                             // gemm_pingpong.hip: 256x256 on 32x32x16 MFMAs

@@ -10,24 +10,33 @@ set is loaded again, and never next to an MFMA of that block."""
 import importlib.util
 import os
 import re
+import sys
 
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-GEN = os.path.join(ROOT, "paper_2108_13191_amd", "csrc", "gen_w4a_loop.py")
+CSRC = os.path.join(ROOT, "paper_2108_13191_amd", "csrc")
 
 
-def _generator():
-    spec = importlib.util.spec_from_file_location("gen_w4a_loop", GEN)
+def _generator(name="gen_w4a_loop"):
+    if CSRC not in sys.path:
+        sys.path.insert(0, CSRC)             # the 128 x 128 generator imports the other one
+    spec = importlib.util.spec_from_file_location(name, os.path.join(CSRC, name + ".py"))
     mod = importlib.util.module_from_spec(spec)
     spec.loader.exec_module(mod)
     return mod
 
 
-def test_committed_include_is_what_the_generator_writes():
-    gen = _generator()
+@pytest.mark.parametrize("name", ["gen_w4a_loop", "gen_w4a128_loop"])
+def test_committed_include_is_what_the_generator_writes(name):
+    gen = _generator(name)
     with open(gen.INC_PATH) as f:
         assert f.read() == gen.render()
+
+
+# what differs between the two tile forms: MFMAs per 32-wide k slice, bytes of an A / a B buffer
+GEOMETRY = {"gen_w4a_loop": dict(slice=64, a_buf=32768, b_buf=32768, ncopy=8),
+            "gen_w4a128_loop": dict(slice=16, a_buf=16384, b_buf=16384, ncopy=4)}
 
 
 A_BASE = 0x100000000 - 4096        # the running A pointer crosses a 32-bit carry
@@ -117,14 +126,17 @@ def _run(lines, kt):
     return trace, nmfma
 
 
-@pytest.mark.parametrize("with_c", [False, True])
-def test_scalar_side_of_the_loop_for_every_trip_count(with_c):
-    gen = _generator()
+@pytest.mark.parametrize("name,with_c", [("gen_w4a_loop", False), ("gen_w4a_loop", True), ("gen_w4a128_loop", False)])
+def test_scalar_side_of_the_loop_for_every_trip_count(name, with_c):
+    gen = _generator(name)
+    geo = GEOMETRY[name]
+    SL, A_BUF, B_BUF, NCOPY = geo["slice"], geo["a_buf"], geo["b_buf"], geo["ncopy"]
+    B_REGION = 2 * A_BUF
     lines = gen.block_c() if with_c else gen.block()
     for kt in range(gen.C_STEPS if with_c else 1, gen.C_STEPS + 14 if with_c else 41):
         trace, nmfma = _run(lines, kt)
         _check_c(gen, trace, with_c)
-        assert nmfma == 128 * kt
+        assert nmfma == 2 * SL * kt
         barriers = [e[0] for e in trace if e[1] == "barrier"]
         assert len(barriers) == kt
         # --- copies: (time, buffer, k step), where they come from and where they land
@@ -133,19 +145,19 @@ def test_scalar_side_of_the_loop_for_every_trip_count(with_c):
             if e[1] != "copy":
                 continue
             t, _, voff, src, m0, at = e
-            j = at // 128                                   # the k step during which it is issued
+            j = (at - 1) // (2 * SL)                        # issued in the shadow of MFMA at - 1: its k step
             want = j + 2 if j + 2 < kt else 0
             d = m0 - LDS_WAVE
             n = int(voff[-2])
             if voff.startswith("%[a_off"):
                 assert src == A_BASE + 128 * want, ("A source", kt, j)
-                assert d == (j % 2) * 32768 + 4096 * n, ("A target", kt, j)
+                assert d == (j % 2) * A_BUF + 4096 * n and n < NCOPY, ("A target", kt, j)
                 copies.append((t, ("A", j % 2), want if j + 2 < kt else None))
             else:
                 assert src == B_BASE + B_STEP * want, ("B source", kt, j)
-                assert d == 65536 + ((j + 2) % 3) * 32768 + 4096 * n, ("B target", kt, j)
+                assert d == B_REGION + ((j + 2) % 3) * B_BUF + 4096 * n and n < NCOPY, ("B target", kt, j)
                 copies.append((t, ("B", (j + 2) % 3), want if j + 2 < kt else None))
-        assert len(copies) == 16 * kt
+        assert len(copies) == 2 * NCOPY * kt
         # the copies the C++ prologue issues before the block (complete, behind a barrier)
         landed = {("A", 0): 0, ("B", 0): 0}
         if kt > 1:
@@ -169,16 +181,18 @@ def test_scalar_side_of_the_loop_for_every_trip_count(with_c):
             if e[1] != "read":
                 continue
             t, _, reg, off, at = e
-            h = -1 if at == 0 else (at - 1) // 64           # issued during slice h: a read of slice h + 1
+            h = -1 if at == 0 else (at - 1) // SL           # issued during slice h: a read of slice h + 1
             step, sl = (h + 1) // 2, (h + 1) % 2
             if reg.startswith("%[a_rd"):
-                assert int(reg[-2]) == sl and off % 2048 == 0 and off % 32768 < 16384
-                buf = ("A", off // 32768)
+                # 16-row blocks of 128-byte rows: 2 KB apart, inside the wavefront's half of the buffer
+                assert int(reg[-2]) == sl and off % 2048 == 0 and off % A_BUF < A_BUF // 2
+                buf = ("A", off // A_BUF)
                 assert buf[1] == step % 2
             else:
+                # slice s = k rows 32s.. of the buffer, second transposing read 4 k rows further
                 full = off + (65536 if reg.startswith("%[b_rdh") else 0)
-                assert full % 32768 in (sl * 16384, sl * 16384 + 2048)
-                buf = ("B", full // 32768)
+                assert full % B_BUF in (sl * (B_BUF // 2), sl * (B_BUF // 2) + B_BUF // 16)
+                buf = ("B", full // B_BUF)
                 assert buf[1] == step % 3
             if step >= kt:
                 continue                                    # fragments nobody multiplies
