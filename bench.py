@@ -59,6 +59,8 @@ def kernel_symbol(tile_name, mode, K=0):
         return f"gemm_pp256_kernel<{ct}, {mi}, {'true' if K % 64 else 'false'}, {bm}, {bn}>"
     if tile_name.startswith("ov"):
         return f"gemm_pp_overlap_kernel<{ct}>"
+    if tile_name.startswith("w4a_128"):
+        return f"gemm_w4a128_kernel<{ct}>"
     if tile_name.startswith("w4a_"):
         return f"gemm_w4a_kernel<{ct}>"
     if tile_name.startswith("w4_"):

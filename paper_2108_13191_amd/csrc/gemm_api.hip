@@ -23,6 +23,7 @@ enum {
     ID_STAG,           // 256 x 256, every other compute unit starts on half a tile
     ID_T64,            // 64 x 64, four LDS stages
     ID_LONG_K,         // 256 x 256, four wavefronts of 128 x 128, k loop in assembly
+    ID_RING128,        // 128 x 128, four wavefronts of 64 x 64, k loop in assembly over five LDS stages
     NUM_PRODUCT
 };
 
@@ -31,7 +32,7 @@ const GemmConfigDesc kGeneric = {
     false, launch_generic, grid_generic};
 
 #ifdef GEMM_F16_LADDER
-constexpr int NUM_LADDER = 11;
+constexpr int NUM_LADDER = 10;
 #else
 constexpr int NUM_LADDER = 0;
 #endif
@@ -50,6 +51,7 @@ const GemmConfigDesc* config(int id)
     case ID_STAG:      return pingpong16_staggered_config();
     case ID_T64:       return tiled_config(64);
     case ID_LONG_K:    return long_k_config();
+    case ID_RING128:   return deep_ring_config();
 #ifdef GEMM_F16_LADDER
     case NUM_PRODUCT + 0: return tiled_config(128);
     case NUM_PRODUCT + 1: return tiled_config(256);
@@ -61,7 +63,6 @@ const GemmConfigDesc* config(int id)
     case NUM_PRODUCT + 7: return interleaved_config();
     case NUM_PRODUCT + 8: return generic_c_in_loop_config();
     case NUM_PRODUCT + 9: return generic_round_per_slice_config();
-    case NUM_PRODUCT + 10: return small_tile_asm_config();
 #endif
     default: return &kGeneric;
     }
@@ -211,6 +212,23 @@ int long_k_if_it_pays(int id, int c_is_f16, int64_t rows, int64_t N, int64_t K)
     return pays ? ID_LONG_K : id;
 }
 
+// At most one 128 x 128 tile per compute unit and 48 or more k steps: the four-wavefront kernel
+// with five LDS stages.  A k step of such a tile is a quarter of a microsecond of MFMAs, less
+// than a copy's way from L2, which the phase-alternating kernel's two or three buffers cannot
+// cover (0.6 us per k step against 0.42 on a full chip, 0.30 on a quarter of it); that kernel
+// in turn starts and ends 2 us sooner (80 KB of LDS: the next launch's workgroups start beside
+// the last one's).  Measured, alternating in one process, f32 / f16 mode: 2048^2, K = 2048: -6 /
+// -2 %, 3072: +3 / +4 %, 4096: +8 / +9 %, 8192: +22 / +21 %; 1536^2 x 3072 +13 / +16 %, 1024 x
+// 2048 x 4096 +22 / +23 %, 1280^2 x 5120 +14 / +15 %, ragged 2000^2 x 4096 +5 / +8 %; the strips
+// behind a split: 256 x 7168^2 +25 / +28 %, 256 x 9216^2 +26 / +27 %, 256 x 15360^2 (bound by
+// the read of B) 0 %.  More than one tile per compute unit (2048 x 4096 x 4096, 2560^2 x 4096):
+// -7 ... -9 %, left where it was.
+int deep_ring_if_it_pays(int id, int64_t rows, int64_t N, int64_t K)
+{
+    if (id != ID_PP128x128) return id;
+    return (K >= 3072 && config(ID_RING128)->grid(rows, N) <= chip().cus) ? ID_RING128 : id;
+}
+
 Plan select_plan_unchained(int c_is_f16, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, int64_t ldc)
 {
     if (!aligned_for_tiled(N, K, A, lda, B, ldb, ldc)) return {ID_GENERIC, M, -1};
@@ -246,7 +264,9 @@ Plan select_plan(int c_is_f16, int64_t M, int64_t N, int64_t K, const void* A, i
     Plan pl = select_plan_unchained(c_is_f16, M, N, K, A, lda, B, ldb, ldc);
     if (g_forced >= 0 && g_forced < num_configs()) return pl;        // a forced configuration runs as it is
     pl.id = long_k_if_it_pays(chained_if_it_pays(pl.id, pl.rows1, N, K), c_is_f16, pl.rows1, N, K);
+    pl.id = deep_ring_if_it_pays(pl.id, pl.rows1, N, K);
     if (pl.id2 >= 0) pl.id2 = long_k_if_it_pays(chained_if_it_pays(pl.id2, M - pl.rows1, N, K), c_is_f16, M - pl.rows1, N, K);
+    if (pl.id2 >= 0) pl.id2 = deep_ring_if_it_pays(pl.id2, M - pl.rows1, N, K);
     return pl;
 }
 

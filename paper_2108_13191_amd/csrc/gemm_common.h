@@ -63,7 +63,7 @@ const GemmConfigDesc* pingpong16_staggered_config();                  // 256x256
 const GemmConfigDesc* long_k_config();                                // 256x256, four wavefronts of 128x128, k loop in assembly
 
 // gemm_w4a128.hip
-const GemmConfigDesc* small_tile_asm_config();                        // 128x128, four wavefronts of 64x64, k loop in assembly
+const GemmConfigDesc* deep_ring_config();                             // 128x128, four wavefronts of 64x64, k loop in assembly over five LDS stages
 
 #ifdef GEMM_F16_LADDER
 // Comparison kernels and ablation rows: built into libgemm_f16_ladder.so only, never selected.

@@ -1,13 +1,14 @@
 // The 128 x 128 x 64 form of the four-wavefront kernel with an assembly k loop (gemm_w4a.hip
-// describes the structure): wavefront tile 64 x 64 = 4 x 4 accumulators, 80 KB of LDS, so that
-// two workgroups fit a compute unit.  It is for problems of a few hundred 128 x 128 tiles, where
-// the phase-alternating kernel of that tile runs one workgroup per compute unit and its
-// barriers (four per k step, with nothing else resident to fill them) cost more than its
-// MFMAs: a wavefront here issues its 32 MFMAs of a k step back to back, with the 24 LDS reads
-// and 8 copies of the step in their shadow and one barrier (gemm_w4a128_loop.inc, written by
-// gen_w4a128_loop.py).
+// describes the structure): wavefront tile 64 x 64 = 4 x 4 accumulators, one workgroup per
+// compute unit.  It is for problems of at most one 128 x 128 tile per compute unit, where the
+// phase-alternating kernel of that tile runs alone on its compute unit and its k step (a
+// quarter of a microsecond of MFMAs) is shorter than the time a copy takes to arrive from L2,
+// which its two or three buffers cannot cover.  Here the LDS is a ring of five stages (160 KB:
+// copies run four k steps ahead), and a wavefront issues its 32 MFMAs of a k step back to
+// back, with the 24 LDS reads and 8 copies of the step in their shadow and one barrier
+// (gemm_w4a128_loop.inc, written by gen_w4a128_loop.py).
 //
-// C is read, added and stored behind the loop.  A k tail (K % 64 != 0) is one unpipelined step
+// C is read before the loop (into registers), added and stored behind it.  A k tail (K % 64 != 0) is one unpipelined step
 // through registers after the loop.  Requirements as for the other tuned kernels: A, B 16-byte
 // aligned; lda, ldb, K, N multiples of 8.  Rows >= M / columns >= N are fetched from clamped
 // addresses and never stored.
@@ -22,8 +23,9 @@ using namespace gemm_dev;
 constexpr int SBM = 128, SBN = 128;
 constexpr int A_BUF = SBM * BK * 2;          // 16 KB
 constexpr int B_BUF = BK * SBN * 2;          // 16 KB
-constexpr int B_REGION = 2 * A_BUF;          // after the two A buffers
-constexpr int W4A128_LDS = 2 * A_BUF + 3 * B_BUF;   // 80 KB
+constexpr int STAGE = A_BUF + B_BUF;         // a stage of the ring: A, then B
+constexpr int STAGES = 5;                    // copies run STAGES - 1 k steps ahead
+constexpr int W4A128_LDS = STAGES * STAGE;   // 160 KB
 constexpr int B_ROW = SBN * 2;               // bytes per k row of a B stage
 constexpr int NCOPY = 4;                     // copies per wavefront per A (or B) stage
 
@@ -104,76 +106,12 @@ __global__ __launch_bounds__(256) void gemm_w4a128_kernel(const TiledParams p)
 #pragma unroll
         for (int fn = 0; fn < 4; fn++) {
             const int chunk = 2 * ((wn_base >> 4) + fn) + ((j & 3) >> 1);   // 16-byte chunk of columns 4(j%4)..+3
-            b_rd[fn] = smem_base + B_REGION + row_off + (uint32_t)((chunk ^ swz) * 16 + 8 * (j & 1));
+            b_rd[fn] = smem_base + A_BUF + row_off + (uint32_t)((chunk ^ swz) * 16 + 8 * (j & 1));
         }
     }
 
-    floatx4 acc[4][4];
-    if (kt_full > 0) {
-        // k steps 0 and 1 into A buffers 0, 1 and B buffers 0, 1; the loop copies from k step 2 on
-        const int first = kt_full < 2 ? kt_full : 2;
-        for (int s = 0; s < first; s++) {
-            const char* const a_src = uniform_ptr128(a_tile + (int64_t)s * BK);
-            const char* const b_src = uniform_ptr128(b_tile + (int64_t)s * BK * p.ldb);
-#pragma unroll
-            for (int t = 0; t < NCOPY; t++) {
-                async_copy16(a_src, a_off[t], lds_wave + s * A_BUF + 4096 * t);
-                async_copy16(b_src, b_off[t], lds_wave + B_REGION + s * B_BUF + 4096 * t);
-            }
-        }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-
-        const uint64_t a_base = (uint64_t)(uintptr_t)a_tile, b_base = (uint64_t)(uintptr_t)b_tile;
-        const uint32_t b_step = (uint32_t)BK * (uint32_t)p.ldb * 2u;                // bytes per k step of B (ldb <= 2^22)
-        const uint64_t a_ptr = a_base + 2 * BK * 2, b_ptr = b_base + 2 * (uint64_t)b_step;
-        const uint32_t a_base_lo = __builtin_amdgcn_readfirstlane((uint32_t)a_base), a_base_hi = __builtin_amdgcn_readfirstlane((uint32_t)(a_base >> 32));
-        const uint32_t b_base_lo = __builtin_amdgcn_readfirstlane((uint32_t)b_base), b_base_hi = __builtin_amdgcn_readfirstlane((uint32_t)(b_base >> 32));
-        const uint32_t a_ptr_lo = __builtin_amdgcn_readfirstlane((uint32_t)a_ptr), a_ptr_hi = __builtin_amdgcn_readfirstlane((uint32_t)(a_ptr >> 32));
-        const uint32_t b_ptr_lo = __builtin_amdgcn_readfirstlane((uint32_t)b_ptr), b_ptr_hi = __builtin_amdgcn_readfirstlane((uint32_t)(b_ptr >> 32));
-        asm volatile(W4A128_LOOP_ASM : W4A128_LOOP_OUTPUTS(acc) : W4A128_LOOP_INPUTS : W4A128_LOOP_CLOBBERS);
-    } else {
-#pragma unroll
-        for (int fm = 0; fm < 4; fm++)
-#pragma unroll
-            for (int fn = 0; fn < 4; fn++) acc[fm][fn] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
-    }
-
-    // ---- k tail: one unpipelined step through registers, zero beyond K ------------------
-    if (p.K % BK != 0) {
-        __builtin_amdgcn_s_barrier();                // every wavefront is out of the loop: the buffers are free
-        const int k0 = kt_full * BK, krem = p.K - k0;
-        const char* a_src = (const char*)(a_tile + k0);
-        const char* b_src = (const char*)(b_tile + (int64_t)k0 * p.ldb);
-#pragma unroll
-        for (int t = 0; t < NCOPY; t++) {
-            uintx4 va = {0u, 0u, 0u, 0u}, vb = {0u, 0u, 0u, 0u};
-            if (8 * a_chunk < krem) va = *reinterpret_cast<const uintx4*>(a_src + a_off[t]);
-            if (b_krow0 + 16 * t < krem) vb = *reinterpret_cast<const uintx4*>(b_src + b_off[t]);
-            *(__attribute__((address_space(3))) uintx4*)(uintptr_t)(lds_wave + 4096 * t + 16 * lane) = va;
-            *(__attribute__((address_space(3))) uintx4*)(uintptr_t)(lds_wave + B_REGION + 4096 * t + 16 * lane) = vb;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int s = 0; s < 2; s++) {
-            half8 fa[4], fb[4];
-#pragma unroll
-            for (int fn = 0; fn < 4; fn++) {
-                const uint32_t addr = b_rd[fn] + s * 32 * B_ROW;
-                fb[fn] = __builtin_shufflevector(lds_read_tr16(addr), lds_read_tr16(addr + 4 * B_ROW), 0, 1, 2, 3, 4, 5, 6, 7);
-            }
-#pragma unroll
-            for (int fm = 0; fm < 4; fm++) fa[fm] = lds_read_b128(a_rd[s] + fm * 16 * (BK * 2));
-#pragma unroll
-            for (int fm = 0; fm < 4; fm++)
-#pragma unroll
-                for (int fn = 0; fn < 4; fn++)
-                    acc[fm][fn] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fb[fn], fa[fm], acc[fm][fn], 0, 0, 0);
-        }
-    }
-
-    // ---- + C, + bias, ReLU, -> C ------------------------------------------------------
+    // ---- C in: fetched first, so that its way from memory overlaps that of the first k steps
+    // (a wavefront alone on its SIMD has the registers: 64 for an f32 tile) ------------------
     // Transposed 16 x 16 blocks (B fragment first): register r of lane l is row l%16, column
     // 4*(l/16) + r of block (fm, fn): one vector access per block.
     CT* const Cbase = (CT*)p.C;
@@ -206,6 +144,73 @@ __global__ __launch_bounds__(256) void gemm_w4a128_kernel(const TiledParams p)
             const uint32_t off = ok ? c_voff + (uint32_t)(fn * 16 * sizeof(CT)) : 0u;
             cin[fm][fn] = *reinterpret_cast<const ctx4*>(rowp + off);
         }
+
+    floatx4 acc[4][4];
+    if (kt_full > 0) {
+        // k steps 0..3 into stages 0..3; the loop copies from k step 4 on
+        const int first = kt_full < STAGES - 1 ? kt_full : STAGES - 1;
+        for (int s = 0; s < first; s++) {
+            const char* const a_src = uniform_ptr128(a_tile + (int64_t)s * BK);
+            const char* const b_src = uniform_ptr128(b_tile + (int64_t)s * BK * p.ldb);
+#pragma unroll
+            for (int t = 0; t < NCOPY; t++) {
+                async_copy16(a_src, a_off[t], lds_wave + s * STAGE + 4096 * t);
+                async_copy16(b_src, b_off[t], lds_wave + s * STAGE + A_BUF + 4096 * t);
+            }
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+
+        const uint64_t a_base = (uint64_t)(uintptr_t)a_tile, b_base = (uint64_t)(uintptr_t)b_tile;
+        const uint32_t b_step = (uint32_t)BK * (uint32_t)p.ldb * 2u;                // bytes per k step of B (ldb <= 2^22)
+        const uint64_t a_ptr = a_base + (STAGES - 1) * BK * 2, b_ptr = b_base + (STAGES - 1) * (uint64_t)b_step;
+        const uint32_t a_base_lo = __builtin_amdgcn_readfirstlane((uint32_t)a_base), a_base_hi = __builtin_amdgcn_readfirstlane((uint32_t)(a_base >> 32));
+        const uint32_t b_base_lo = __builtin_amdgcn_readfirstlane((uint32_t)b_base), b_base_hi = __builtin_amdgcn_readfirstlane((uint32_t)(b_base >> 32));
+        const uint32_t a_ptr_lo = __builtin_amdgcn_readfirstlane((uint32_t)a_ptr), a_ptr_hi = __builtin_amdgcn_readfirstlane((uint32_t)(a_ptr >> 32));
+        const uint32_t b_ptr_lo = __builtin_amdgcn_readfirstlane((uint32_t)b_ptr), b_ptr_hi = __builtin_amdgcn_readfirstlane((uint32_t)(b_ptr >> 32));
+        asm volatile(W4A128_LOOP_ASM : W4A128_LOOP_OUTPUTS(acc) : W4A128_LOOP_INPUTS : W4A128_LOOP_CLOBBERS);
+    } else {
+#pragma unroll
+        for (int fm = 0; fm < 4; fm++)
+#pragma unroll
+            for (int fn = 0; fn < 4; fn++) acc[fm][fn] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+    }
+
+    // ---- k tail: one unpipelined step through registers, zero beyond K ------------------
+    if (p.K % BK != 0) {
+        __builtin_amdgcn_s_barrier();                // every wavefront is out of the loop and its copies have landed: stage 0 is free
+        const int k0 = kt_full * BK, krem = p.K - k0;
+        const char* a_src = (const char*)(a_tile + k0);
+        const char* b_src = (const char*)(b_tile + (int64_t)k0 * p.ldb);
+#pragma unroll
+        for (int t = 0; t < NCOPY; t++) {
+            uintx4 va = {0u, 0u, 0u, 0u}, vb = {0u, 0u, 0u, 0u};
+            if (8 * a_chunk < krem) va = *reinterpret_cast<const uintx4*>(a_src + a_off[t]);
+            if (b_krow0 + 16 * t < krem) vb = *reinterpret_cast<const uintx4*>(b_src + b_off[t]);
+            *(__attribute__((address_space(3))) uintx4*)(uintptr_t)(lds_wave + 4096 * t + 16 * lane) = va;
+            *(__attribute__((address_space(3))) uintx4*)(uintptr_t)(lds_wave + A_BUF + 4096 * t + 16 * lane) = vb;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < 2; s++) {
+            half8 fa[4], fb[4];
+#pragma unroll
+            for (int fn = 0; fn < 4; fn++) {
+                const uint32_t addr = b_rd[fn] + s * 32 * B_ROW;
+                fb[fn] = __builtin_shufflevector(lds_read_tr16(addr), lds_read_tr16(addr + 4 * B_ROW), 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+#pragma unroll
+            for (int fm = 0; fm < 4; fm++) fa[fm] = lds_read_b128(a_rd[s] + fm * 16 * (BK * 2));
+#pragma unroll
+            for (int fm = 0; fm < 4; fm++)
+#pragma unroll
+                for (int fn = 0; fn < 4; fn++)
+                    acc[fm][fn] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fb[fn], fa[fm], acc[fm][fn], 0, 0, 0);
+        }
+    }
+
+    // ---- + C, + bias, ReLU, -> C ------------------------------------------------------
 #pragma unroll
     for (int fm = 0; fm < 4; fm++) {
         char* rowp = reinterpret_cast<char*>(Cbase + (int64_t)(c_row0 + fm * 16) * p.ldc + c_col0);
@@ -244,4 +249,4 @@ const GemmConfigDesc kW4a128 = {
 
 }  // namespace
 
-const GemmConfigDesc* small_tile_asm_config() { return &kW4a128; }
+const GemmConfigDesc* deep_ring_config() { return &kW4a128; }

@@ -1,6 +1,7 @@
-"""GPU parity of what is particular to the long-k kernel (four wavefronts of 128 x 128, k loop in
-assembly): leaving the loop at each of its exits, C read inside the loop, and where the
-selector takes it.  The tests over all configurations (test_gpu_parity.py,
+"""GPU parity of what is particular to the two kernels with an assembly k loop (four wavefronts of
+128 x 128 on a 256 x 256 tile: the long-k kernel; of 64 x 64 on a 128 x 128 tile over five LDS
+stages): leaving the loop at each of its exits, C read inside the loop, and where the selector
+takes them.  The tests over all configurations (test_gpu_parity.py,
 test_gpu_fused_epilogue.py) cover it like every other product kernel."""
 import numpy as np
 import pytest
@@ -16,6 +17,7 @@ from gpu_util import run_gemm, assert_close, config_id       # noqa: E402
 
 CDT = {"f32": np.float32, "f16": np.float16}
 NAME = "w4a_256x256x64"
+NAME128 = "w4a_128x128x64"
 
 
 @pytest.fixture(autouse=True)
@@ -79,3 +81,38 @@ def test_selected_for_long_k_loops_and_right_there(oracle_mod):
     assert binding.query_config(0, 8192, 8192, 8192, 16, 8192, 16, 8192, 16, 8192)["name"].endswith("_chain")
     for n in (12288, 16384):
         assert binding.query_config(0, n, n, n, 16, n, 16, n, 16, n)["name"] == NAME
+
+
+def test_five_stage_k_loop_at_every_exit(oracle_mod):
+    """The 128 x 128 kernel's assembly k loop is unrolled five k steps deep (one per LDS stage),
+    with copies four k steps ahead: 1 to 14 full k steps, with and without a k tail, several
+    tiles with ragged edges, both modes; integers."""
+    binding.force_config(config_id(NAME128))
+    for steps in range(1, 15):
+        for tail in (0, 24):
+            M, N, K = 300, 264, 64 * steps + tail
+            A, B, _ = wl.make_inputs(M, N, K, "int2", "zeros", seed=700 + steps)
+            for mode in ("f32", "f16"):
+                C0 = np.random.default_rng(steps).integers(-4, 5, size=(M, N)).astype(CDT[mode])
+                got = run_gemm(A, B, C0, mode)
+                Cref, _ = oracle_mod.gemm_f16(A, B, C0)
+                want = oracle_mod.round_to_f32(Cref) if mode == "f32" else Cref.astype(np.float16)
+                assert np.array_equal(got, want), f"K = {K} {mode}"
+
+
+def test_five_stage_kernel_selected_for_few_tiles_and_a_long_k_loop(oracle_mod):
+    """At most one 128 x 128 tile per compute unit and K >= 3072: the five-stage kernel, also for
+    the strip behind a split; sampled rows of such a problem against the oracle, both modes."""
+    M, N, K = 2048, 1920, 4096
+    for mode in ("f32", "f16"):
+        q = binding.query_config(mode == "f16", M, N, K, 16, K, 16, N, 16, N)
+        assert q["name"] == NAME128, q
+        A, B, C0 = wl.make_inputs(M, N, K, "normal_rsqrtk", "uniform", seed=41, c_dtype=CDT[mode])
+        got = run_gemm(A, B, C0, mode)
+        rows = np.array([0, 1, 63, 64, 127, 128, 300, 1023, 1024, 2047])
+        Cref, S = oracle_mod.gemm_f16(A, B, C0, rows=rows)
+        assert_close(got[rows], Cref, S, C0[rows], mode, what=f"five stages, auto {mode}")
+    assert binding.query_config(0, 2048, 2048, 2048, 16, 2048, 16, 2048, 16, 2048)["name"].startswith("pp128x128")
+    assert binding.query_config(0, 2048, 4096, 4096, 16, 4096, 16, 4096, 16, 4096)["name"] != NAME128
+    q = binding.query_config(0, 7168, 7168, 7168, 16, 7168, 16, 7168, 16, 7168)
+    assert q["split_rows"] == 6912 and q["id2"] == config_id(NAME128), q

@@ -34,9 +34,29 @@ def test_committed_include_is_what_the_generator_writes(name):
         assert f.read() == gen.render()
 
 
-# what differs between the two tile forms: MFMAs per 32-wide k slice, bytes of an A / a B buffer
-GEOMETRY = {"gen_w4a_loop": dict(slice=64, a_buf=32768, b_buf=32768, ncopy=8),
-            "gen_w4a128_loop": dict(slice=16, a_buf=16384, b_buf=16384, ncopy=4)}
+# What differs between the two tile forms: MFMAs per 32-wide k slice, bytes of an A / a B buffer,
+# copies per wavefront and buffer, how many k steps ahead the copies run, and the LDS map:
+# buffer_of(kind, k step) -> (buffer key, its byte offset in the LDS); reg_base(register name) ->
+# the LDS offset that the address register points at.
+def _w4a_buffer(kind, step):
+    return (("A", step % 2), (step % 2) * 32768) if kind == "A" else (("B", step % 3), 65536 + (step % 3) * 32768)
+
+
+def _w4a_reg_base(reg):
+    return 0 if reg.startswith("%[a_rd") else 65536 + (65536 if reg.startswith("%[b_rdh") else 0)
+
+
+def _w4a128_buffer(kind, step):
+    return ((kind, step % 5), (step % 5) * 32768 + (0 if kind == "A" else 16384))
+
+
+def _w4a128_reg_base(reg):
+    name = reg[2:-1].rstrip("0123456789")
+    return {"a_rd": 0, "a_rdm": 65536, "a_rdh": 131072, "b_rd": 16384, "b_rdm": 16384 + 65536, "b_rdh": 16384 + 131072}[name]
+
+
+GEOMETRY = {"gen_w4a_loop": dict(slice=64, a_buf=32768, b_buf=32768, ncopy=8, ahead=2, buffer_of=_w4a_buffer, reg_base=_w4a_reg_base),
+            "gen_w4a128_loop": dict(slice=16, a_buf=16384, b_buf=16384, ncopy=4, ahead=4, buffer_of=_w4a128_buffer, reg_base=_w4a128_reg_base)}
 
 
 A_BASE = 0x100000000 - 4096        # the running A pointer crosses a 32-bit carry
@@ -48,13 +68,13 @@ C_BYTES = 0x12345678
 LDS_WAVE = 3072
 
 
-def _run(lines, kt):
+def _run(lines, kt, ahead):
     """Execute the block's scalar instructions; return the trace of copies, reads, barriers."""
     labels = {ln[:-1]: i for i, ln in enumerate(lines) if ln.endswith(":")}
     S = {"%[kt]": kt, "%[b_step]": B_STEP, "%[lds_wave]": LDS_WAVE,
          "%[a_base_lo]": A_BASE & 0xffffffff, "%[a_base_hi]": A_BASE >> 32,
          "%[b_base_lo]": B_BASE & 0xffffffff, "%[b_base_hi]": B_BASE >> 32}
-    ap, bp = A_BASE + 2 * 128, B_BASE + 2 * B_STEP
+    ap, bp = A_BASE + ahead * 128, B_BASE + ahead * B_STEP
     S.update({"%[a_ptr_lo]": ap & 0xffffffff, "%[a_ptr_hi]": ap >> 32, "%[b_ptr_lo]": bp & 0xffffffff, "%[b_ptr_hi]": bp >> 32})
     S.update({"%[c_lo]": C_BASE & 0xffffffff, "%[c_hi]": C_BASE >> 32, "%[c_rowstep]": C_ROWSTEP, "%[c_bytes]": C_BYTES})
 
@@ -130,11 +150,11 @@ def _run(lines, kt):
 def test_scalar_side_of_the_loop_for_every_trip_count(name, with_c):
     gen = _generator(name)
     geo = GEOMETRY[name]
-    SL, A_BUF, B_BUF, NCOPY = geo["slice"], geo["a_buf"], geo["b_buf"], geo["ncopy"]
-    B_REGION = 2 * A_BUF
+    SL, A_BUF, B_BUF, NCOPY, AHEAD = geo["slice"], geo["a_buf"], geo["b_buf"], geo["ncopy"], geo["ahead"]
+    buffer_of, reg_base = geo["buffer_of"], geo["reg_base"]
     lines = gen.block_c() if with_c else gen.block()
     for kt in range(gen.C_STEPS if with_c else 1, gen.C_STEPS + 14 if with_c else 41):
-        trace, nmfma = _run(lines, kt)
+        trace, nmfma = _run(lines, kt, AHEAD)
         _check_c(gen, trace, with_c)
         assert nmfma == 2 * SL * kt
         barriers = [e[0] for e in trace if e[1] == "barrier"]
@@ -146,22 +166,19 @@ def test_scalar_side_of_the_loop_for_every_trip_count(name, with_c):
                 continue
             t, _, voff, src, m0, at = e
             j = (at - 1) // (2 * SL)                        # issued in the shadow of MFMA at - 1: its k step
-            want = j + 2 if j + 2 < kt else 0
+            want = j + AHEAD if j + AHEAD < kt else 0
             d = m0 - LDS_WAVE
             n = int(voff[-2])
-            if voff.startswith("%[a_off"):
-                assert src == A_BASE + 128 * want, ("A source", kt, j)
-                assert d == (j % 2) * A_BUF + 4096 * n and n < NCOPY, ("A target", kt, j)
-                copies.append((t, ("A", j % 2), want if j + 2 < kt else None))
-            else:
-                assert src == B_BASE + B_STEP * want, ("B source", kt, j)
-                assert d == B_REGION + ((j + 2) % 3) * B_BUF + 4096 * n and n < NCOPY, ("B target", kt, j)
-                copies.append((t, ("B", (j + 2) % 3), want if j + 2 < kt else None))
+            kind = "A" if voff.startswith("%[a_off") else "B"
+            buf, where = buffer_of(kind, j + AHEAD)
+            assert src == (A_BASE + 128 * want if kind == "A" else B_BASE + B_STEP * want), (kind, "source", kt, j)
+            assert d == where + 4096 * n and n < NCOPY, (kind, "target", kt, j)
+            copies.append((t, buf, want if j + AHEAD < kt else None))
         assert len(copies) == 2 * NCOPY * kt
         # the copies the C++ prologue issues before the block (complete, behind a barrier)
-        landed = {("A", 0): 0, ("B", 0): 0}
-        if kt > 1:
-            landed.update({("A", 1): 1, ("B", 1): 1})
+        landed = {}
+        for step in range(min(kt, AHEAD)):
+            landed.update({buffer_of("A", step)[0]: step, buffer_of("B", step)[0]: step})
         # --- a copy has landed for every wavefront once a wait that leaves fewer vector-memory
         # operations outstanding than were issued after it is followed by a barrier
         vmem = [e[0] for e in trace if e[1] in ("copy", "cload")]
@@ -183,17 +200,15 @@ def test_scalar_side_of_the_loop_for_every_trip_count(name, with_c):
             t, _, reg, off, at = e
             h = -1 if at == 0 else (at - 1) // SL           # issued during slice h: a read of slice h + 1
             step, sl = (h + 1) // 2, (h + 1) % 2
-            if reg.startswith("%[a_rd"):
+            kind = "A" if reg.startswith("%[a_rd") else "B"
+            buf, where = buffer_of(kind, step)
+            within = reg_base(reg) + off - where             # the read lies in the buffer of its k step
+            if kind == "A":
                 # 16-row blocks of 128-byte rows: 2 KB apart, inside the wavefront's half of the buffer
-                assert int(reg[-2]) == sl and off % 2048 == 0 and off % A_BUF < A_BUF // 2
-                buf = ("A", off // A_BUF)
-                assert buf[1] == step % 2
+                assert int(reg[-2]) == sl and within % 2048 == 0 and 0 <= within < A_BUF // 2
             else:
                 # slice s = k rows 32s.. of the buffer, second transposing read 4 k rows further
-                full = off + (65536 if reg.startswith("%[b_rdh") else 0)
-                assert full % B_BUF in (sl * (B_BUF // 2), sl * (B_BUF // 2) + B_BUF // 16)
-                buf = ("B", full // B_BUF)
-                assert buf[1] == step % 3
+                assert within in (sl * (B_BUF // 2), sl * (B_BUF // 2) + B_BUF // 16)
             if step >= kt:
                 continue                                    # fragments nobody multiplies
             # the last copy into this buffer issued before the read holds this k step and has landed
