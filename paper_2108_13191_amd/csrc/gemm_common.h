@@ -68,6 +68,7 @@ const GemmConfigDesc* deep_ring_config();                             // 128x128
 #ifdef GEMM_F16_LADDER
 // Comparison kernels and ablation rows: built into libgemm_f16_ladder.so only, never selected.
 const GemmConfigDesc* pingpong_config();                             // gemm_pingpong.hip: 256x256 on 32x32x16 MFMAs
+const GemmConfigDesc* pingpong16_192x192_config();                   // gemm_pingpong.hip: 192x192 tile (fills 256 compute units where 192x256 fills 192)
 const GemmConfigDesc* pingpong16_no_xcd_order_config();              // gemm_pingpong.hip: tiles dealt to XCDs as the hardware deals workgroups
 const GemmConfigDesc* tiled_no_swizzle_config();                     // gemm_tiled.hip: 256x256, LDS image not swizzled
 const GemmConfigDesc* generic_c_in_loop_config();                    // gemm_generic.hip: C read and written in every k step

@@ -734,6 +734,8 @@ const GemmConfigDesc kPingPong16Persistent = {
 int launch_pp_no_xcd_order(const GemmArgs& a) { return launch_pp<16, 256, 256>(a, false); }
 const GemmConfigDesc kPingPong = {
     "pp256x256x64_w2x4", 256, 256, BK, 8, 128, 64, lds_pp(256, 256), true, launch_pp_plain<32, 256, 256>, grid_pp<256, 256>};
+const GemmConfigDesc kPingPong16_192x192 = {
+    "pp192x192x64_w2x4_mi16", 192, 192, BK, 8, 96, 48, lds_pp(192, 192), true, launch_pp_plain<16, 192, 192>, grid_pp<192, 192>};
 const GemmConfigDesc kPingPong16NoXcd = {
     "pp256x256x64_w2x4_mi16_noxcd", 256, 256, BK, 8, 128, 64, lds_pp(256, 256), true, launch_pp_no_xcd_order, grid_pp<256, 256>};
 #endif
@@ -751,4 +753,5 @@ const GemmConfigDesc* pingpong16_config(int bm, int bn)
 #ifdef GEMM_F16_LADDER
 const GemmConfigDesc* pingpong_config() { return &kPingPong; }
 const GemmConfigDesc* pingpong16_no_xcd_order_config() { return &kPingPong16NoXcd; }
+const GemmConfigDesc* pingpong16_192x192_config() { return &kPingPong16_192x192; }
 #endif
