@@ -213,21 +213,25 @@ int long_k_if_it_pays(int id, int c_is_f16, int64_t rows, int64_t N, int64_t K)
     return pays ? ID_LONG_K : id;
 }
 
-// At most one 128 x 128 tile per compute unit and 48 or more k steps: the four-wavefront kernel
+// At most one 128 x 128 tile per compute unit and 96 or more k steps: the four-wavefront kernel
 // with five LDS stages.  A k step of such a tile is a quarter of a microsecond of MFMAs, less
 // than a copy's way from L2, which the phase-alternating kernel's two or three buffers cannot
 // cover (0.6 us per k step against 0.42 on a full chip, 0.30 on a quarter of it); that kernel
-// in turn starts and ends 2 us sooner (80 KB of LDS: the next launch's workgroups start beside
-// the last one's).  Measured, alternating in one process, f32 / f16 mode: 2048^2, K = 2048: -6 /
-// -2 %, 3072: +3 / +4 %, 4096: +8 / +9 %, 8192: +22 / +21 %; 1536^2 x 3072 +13 / +16 %, 1024 x
-// 2048 x 4096 +22 / +23 %, 1280^2 x 5120 +14 / +15 %, ragged 2000^2 x 4096 +5 / +8 %; the strips
-// behind a split: 256 x 7168^2 +25 / +28 %, 256 x 9216^2 +26 / +27 %, 256 x 15360^2 (bound by
-// the read of B) 0 %.  More than one tile per compute unit (2048 x 4096 x 4096, 2560^2 x 4096):
-// -7 ... -9 %, left where it was.
+// in turn starts and ends sooner (80 KB of LDS: the next launch's workgroups start beside the
+// last one's).  Measured, alternating in one process on the same operands (they stay in the
+// last-level cache), f32 / f16 mode: 2048^2, K = 2048: -6 / -2 %, 3072: +3 / +4 %, 4096: +8 /
+// +9 %, 8192: +22 / +21 %; 1536^2 x 3072 +13 / +16 %, 1024 x 2048 x 4096 +22 / +23 %, 1280^2 x
+// 5120 +14 / +15 %, ragged 2000^2 x 4096 +5 / +8 %; the strips behind a split: 256 x 7168^2
+// +25 / +28 %, 256 x 9216^2 +26 / +27 %, 256 x 15360^2 (bound by the read of B) 0 %.  More than
+// one tile per compute unit (2048 x 4096 x 4096, 2560^2 x 4096): -7 ... -9 %.  With operand
+// sets rotating so that every launch reads A and B from HBM its k step is 0.50 us against
+// 0.56, but its start costs 5 us more: 2048^2, K = 3072: -8 / -4 %, 4096: -3 / 0 %, 6144: -3 /
+// -0.5 %, 8192: +3 / +5 %; 1536^2 x 3072 -6 / -5 %; 256 x 7168^2 -3 %.  From K = 6144 on what
+// it gains on cached operands (+15 % and more) outweighs what it loses on cold ones.
 int deep_ring_if_it_pays(int id, int64_t rows, int64_t N, int64_t K)
 {
     if (id != ID_PP128x128) return id;
-    return (K >= 3072 && config(ID_RING128)->grid(rows, N) <= chip().cus) ? ID_RING128 : id;
+    return (K >= 6144 && config(ID_RING128)->grid(rows, N) <= chip().cus) ? ID_RING128 : id;
 }
 
 Plan select_plan_unchained(int c_is_f16, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, int64_t ldc)

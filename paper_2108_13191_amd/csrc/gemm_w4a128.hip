@@ -147,18 +147,22 @@ __global__ __launch_bounds__(256) void gemm_w4a128_kernel(const TiledParams p)
 
     floatx4 acc[4][4];
     if (kt_full > 0) {
-        // k steps 0..3 into stages 0..3; the loop copies from k step 4 on
-        const int first = kt_full < STAGES - 1 ? kt_full : STAGES - 1;
-        for (int s = 0; s < first; s++) {
-            const char* const a_src = uniform_ptr128(a_tile + (int64_t)s * BK);
-            const char* const b_src = uniform_ptr128(b_tile + (int64_t)s * BK * p.ldb);
+        // k steps 0..3 into stages 0..3 (a k step beyond the last one: k step 0 once more, which
+        // nobody reads; the loop's waits count on 8 copies per stage); the loop copies from k
+        // step 4 on.  Only k step 0 (and C, requested before it) is waited for here: the wait
+        // in the middle of k step j leaves the 20 copies behind those of step j + 1 in flight,
+        // which holds from j = 0 on with steps 2, 3 and half of 4 behind step 1.
 #pragma unroll
-            for (int t = 0; t < NCOPY; t++) {
-                async_copy16(a_src, a_off[t], lds_wave + s * STAGE + 4096 * t);
-                async_copy16(b_src, b_off[t], lds_wave + s * STAGE + A_BUF + 4096 * t);
-            }
+        for (int s = 0; s < STAGES - 1; s++) {
+            const int ks = s < kt_full ? s : 0;
+            const char* const a_src = uniform_ptr128(a_tile + (int64_t)ks * BK);
+            const char* const b_src = uniform_ptr128(b_tile + (int64_t)ks * BK * p.ldb);
+#pragma unroll
+            for (int t = 0; t < NCOPY; t++) async_copy16(a_src, a_off[t], lds_wave + s * STAGE + 4096 * t);
+#pragma unroll
+            for (int t = 0; t < NCOPY; t++) async_copy16(b_src, b_off[t], lds_wave + s * STAGE + A_BUF + 4096 * t);
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
 

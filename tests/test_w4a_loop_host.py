@@ -35,7 +35,8 @@ def test_committed_include_is_what_the_generator_writes(name):
 
 
 # What differs between the two tile forms: MFMAs per 32-wide k slice, bytes of an A / a B buffer,
-# copies per wavefront and buffer, how many k steps ahead the copies run, and the LDS map:
+# copies per wavefront and buffer, how many k steps ahead the copies run, whether the C++ prologue
+# waits for all of its copies or only for those of k step 0 (`waited`), and the LDS map:
 # buffer_of(kind, k step) -> (buffer key, its byte offset in the LDS); reg_base(register name) ->
 # the LDS offset that the address register points at.
 def _w4a_buffer(kind, step):
@@ -55,8 +56,8 @@ def _w4a128_reg_base(reg):
     return {"a_rd": 0, "a_rdm": 65536, "a_rdh": 131072, "b_rd": 16384, "b_rdm": 16384 + 65536, "b_rdh": 16384 + 131072}[name]
 
 
-GEOMETRY = {"gen_w4a_loop": dict(slice=64, a_buf=32768, b_buf=32768, ncopy=8, ahead=2, buffer_of=_w4a_buffer, reg_base=_w4a_reg_base),
-            "gen_w4a128_loop": dict(slice=16, a_buf=16384, b_buf=16384, ncopy=4, ahead=4, buffer_of=_w4a128_buffer, reg_base=_w4a128_reg_base)}
+GEOMETRY = {"gen_w4a_loop": dict(slice=64, a_buf=32768, b_buf=32768, ncopy=8, ahead=2, waited="all", buffer_of=_w4a_buffer, reg_base=_w4a_reg_base),
+            "gen_w4a128_loop": dict(slice=16, a_buf=16384, b_buf=16384, ncopy=4, ahead=4, waited="first", buffer_of=_w4a128_buffer, reg_base=_w4a128_reg_base)}
 
 
 A_BASE = 0x100000000 - 4096        # the running A pointer crosses a 32-bit carry
@@ -175,13 +176,23 @@ def test_scalar_side_of_the_loop_for_every_trip_count(name, with_c):
             assert d == where + 4096 * n and n < NCOPY, (kind, "target", kt, j)
             copies.append((t, buf, want if j + AHEAD < kt else None))
         assert len(copies) == 2 * NCOPY * kt
-        # the copies the C++ prologue issues before the block (complete, behind a barrier)
+        issued_in_block = len(copies)
+        # The copies the C++ prologue issues before the block: all complete and behind a barrier
+        # ("all": k steps 0 .. min(kt, AHEAD) - 1), or ("first") only those of k step 0, the
+        # others -- always AHEAD - 1 further k steps, beyond the last one k step 0 once more --
+        # still in flight in front of the block's own copies, A then B of each k step.
         landed = {}
-        for step in range(min(kt, AHEAD)):
-            landed.update({buffer_of("A", step)[0]: step, buffer_of("B", step)[0]: step})
+        in_flight = []
+        for step in range(AHEAD if geo["waited"] == "first" else min(kt, AHEAD)):
+            for kind in ("A", "B"):
+                if step == 0 or geo["waited"] == "all":
+                    landed[buffer_of(kind, step)[0]] = step
+                else:
+                    in_flight += [(buffer_of(kind, step)[0], step if step < kt else None)] * NCOPY
+        copies = [(i - len(in_flight), buf, step) for i, (buf, step) in enumerate(in_flight)] + copies
         # --- a copy has landed for every wavefront once a wait that leaves fewer vector-memory
         # operations outstanding than were issued after it is followed by a barrier
-        vmem = [e[0] for e in trace if e[1] in ("copy", "cload")]
+        vmem = [c[0] for c in copies[:len(copies) - issued_in_block]] + [e[0] for e in trace if e[1] in ("copy", "cload")]
 
         def landed_at(copy_index):
             t_issue = copies[copy_index][0]
