@@ -126,27 +126,33 @@ struct Cand { int id; double eff; int per_cu; };
 // The 192- and 128-row forms reuse operands less per tile, but e.g. 6144^3 is exactly three
 // rounds of 192 x 256 tiles instead of 2.25 of 256 x 256.  The 128 x 128 form runs two
 // workgroups per compute unit, which hide each other's prologue and epilogue: the choice for
-// problems of a few hundred tiles.  256 x 192 serves N = 768 and the like: per tile area it is
-// as fast as 256 x 256, but a round that fills all compute units runs at a lower clock than one
-// that leaves some idle, so that filling the chip pays less than the round count says -- hence
-// 0.8.  eff = measured throughput per unit of tile area relative to the 256 x 256 tile.
-const Cand kCands[] = {{ID_PP256, 1.0, 1}, {ID_PP192, 0.87, 1}, {ID_PP128, 0.78, 1}, {ID_PP256x192, 0.8, 1},
+// problems of a few hundred tiles.  256 x 192 serves N = 768 and the like.  eff = measured
+// throughput per unit of tile area relative to the 256 x 256 tile, over whole rounds.
+const Cand kCands[] = {{ID_PP256, 1.0, 1}, {ID_PP192, 0.95, 1}, {ID_PP128, 0.85, 1}, {ID_PP256x192, 0.9, 1},
                        {ID_PP128x128, 0.9, 2}, {ID_T64, 0.4, 4}};
 
 // Estimated time of one launch in units of tile area: the rounds the grid needs
 // on the device's compute units times the work of one tile, divided by the
 // configuration's efficiency (large tiles reuse operands better; small tiles
 // fill the chip on small problems -- the trade-off the paper reports in
-// section Mixed Precision Performance).  A partial round costs a full one,
-// except that workgroups which would share a compute unit and do not have to
-// (the last round has fewer than 256 x per_cu of them) run somewhat faster.
+// section Mixed Precision Performance).  Behind at least one full round, a partial round of
+// the one-workgroup-per-unit kernels costs half a round plus half its fill (a problem of less
+// than one round pays a whole one, unless it is the second launch of a split: alone it is
+// bound by latencies, not by power): the part runs at its power limit, and
+// compute units that idle leave their share to the clock of the others (measured on 25
+// problems of 100 to 1600 tiles of 256 x 256, in rounds of that tile: 16 tiles left over
+// +0.55, 64 +0.6 ... 0.7, 128 +0.8 ... 0.9, 228 +0.9; counting a partial round as a full one
+// chose a plan 6 to 10 % slower than the best on 4608^3, 3072 x 8192 x 4096, 6144 x 4096 x
+// 2048, 8192 x 2560 x 8192).  With several workgroups per unit, those which would share a
+// compute unit and do not have to (the last round has fewer than 256 x per_cu of them) run
+// somewhat faster.
 // The 128 x 128 form's two workgroups per compute unit hide each other's
 // prologue and epilogue, which counts for more the shorter the k loop is.
 // The 64 x 64 tiling moves f16 C two bytes per lane: on problems of 512^2 results and more with
 // k loops up to 2048 its f16 mode falls behind the 128 x 128 form (measured 25 / 62 / 78 / 123
 // against 29 / 75 / 104 / 146 TFLOP/s at 512^3, 768^3, 1024^2 x 512, 1024^3; in f32 mode, and at
 // K = 4096 in both, it stays ahead).
-double launch_cost(const Cand& c, int c_is_f16, int64_t M, int64_t N, int64_t K)
+double launch_cost(const Cand& c, int c_is_f16, int64_t M, int64_t N, int64_t K, bool behind_full_rounds)
 {
     const GemmConfigDesc* d = config(c.id);
     const int64_t g = d->grid(M, N);
@@ -157,16 +163,17 @@ double launch_cost(const Cand& c, int c_is_f16, int64_t M, int64_t N, int64_t K)
     const int64_t cus = chip().cus, slots = cus * c.per_cu;
     const int64_t full = g / slots, left = g % slots;
     const double sharing = (double)((left + cus - 1) / cus);                   // workgroups per compute unit in the last round
-    const double last = left ? (0.5 + 0.5 * sharing / c.per_cu) * c.per_cu : 0.0;
+    const double last = !left ? 0.0 : (c.per_cu == 1 && (full >= 1 || behind_full_rounds)) ? 0.5 + 0.5 * (double)left / (double)cus
+                                                                   : (0.5 + 0.5 * sharing / c.per_cu) * c.per_cu;
     return ((double)full * c.per_cu + last) * (double)d->block_m * d->block_n / eff;
 }
 
-int best_single(int c_is_f16, int64_t M, int64_t N, int64_t K, double* cost_out)
+int best_single(int c_is_f16, int64_t M, int64_t N, int64_t K, double* cost_out, bool behind_full_rounds = false)
 {
     int best = ID_PP256;
     double best_cost = -1.0;
     for (const Cand& c : kCands) {
-        const double cost = launch_cost(c, c_is_f16, M, N, K);
+        const double cost = launch_cost(c, c_is_f16, M, N, K, behind_full_rounds);
         if (cost < 0) continue;
         if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = c.id; }
     }
@@ -246,10 +253,13 @@ Plan select_plan_unchained(int c_is_f16, int64_t M, int64_t N, int64_t K, const 
     // most half full: the staggered form fills that round with half tiles (and
     // spreads the C traffic, which dominates such problems, over time).  With long
     // k loops the two halves of the chip would no longer share operand panels in L2.
+    // Such problems are bound by the traffic of C, and no plan of two launches is tried for
+    // them: (16384,2304,768) 80 us against 84 ... 87 on 256 x 192 tiles (three whole rounds),
+    // 90 chained, 86 for a row split.
     {
         const int64_t tiles = tiles_m * tiles_n, full = tiles / cus, left = tiles % cus;
-        const double staggered = ((double)full + 0.55) * 65536.0;
-        if (cus == 256 && K <= 1024 && full >= 2 && left > 0 && left <= 128 && staggered < cost) { cost = staggered; best = {id_staggered(), M, -1}; }
+        const double staggered = ((double)full + 0.4) * 65536.0;
+        if (cus == 256 && K <= 1024 && full >= 2 && left > 0 && left <= 128 && staggered < cost) return {id_staggered(), M, -1};
     }
     const double second_launch = 3000.0;                  // drain and refill between the two launches
     const int64_t total_rounds = (tiles_m * tiles_n + cus - 1) / cus;
@@ -257,8 +267,9 @@ Plan select_plan_unchained(int c_is_f16, int64_t M, int64_t N, int64_t K, const 
         const int64_t j = (r * cus) / tiles_n;             // tile rows that fit r rounds
         if (j < 1 || j >= tiles_m) continue;
         double rest = 0;
-        const int id2 = best_single(c_is_f16, M - 256 * j, N, K, &rest);
-        const double first = (double)((j * tiles_n + cus - 1) / cus) * 65536.0;
+        const int id2 = best_single(c_is_f16, M - 256 * j, N, K, &rest, true);
+        const int64_t t1 = j * tiles_n;                     // tiles of the first launch: whole rounds and a partial one, as in launch_cost
+        const double first = ((double)(t1 / cus) + (t1 % cus ? 0.5 + 0.5 * (double)(t1 % cus) / (double)cus : 0.0)) * 65536.0;
         if (rest >= 0 && first + rest + second_launch < cost) { cost = first + rest + second_launch; best = {ID_PP256, 256 * j, id2}; }
     }
     return best;

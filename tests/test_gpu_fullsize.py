@@ -126,7 +126,7 @@ def test_auto_selection_on_random_mid_size_shapes(oracle_mod):
     shapes = [(int(rng.integers(2, 80)) * 128 - int(rng.integers(0, 2)) * int(rng.integers(1, 100)),
                int(rng.integers(16, 900)) * 8,
                int(rng.integers(8, 160)) * 8) for _ in range(14)]
-    shapes += [(16384, 2304, 512), (9216, 9216, 256), (7168, 7168, 192), (5120, 5120, 320)]   # staggered / split plans for certain
+    shapes += [(16384, 2304, 512), (9216, 9216, 256), (7168, 7168, 192), (5120, 5120, 320), (8192, 4096, 320)]   # staggered / split / chained plans for certain
     for idx, (M, N, K) in enumerate(shapes):
         mode = "f32" if idx % 2 == 0 else "f16"
         A, B, C0 = wl.make_inputs(M, N, K, "uniform", "uniform", seed=500 + idx, c_dtype=CDT[mode])

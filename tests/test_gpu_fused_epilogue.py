@@ -131,7 +131,7 @@ def test_errors():
 
 def test_fused_epilogue_on_a_row_split_plan(oracle_mod):
     """Both launches of a split plan apply the same bias and activation."""
-    M, N, K = 4300, 4352, 192
+    M, N, K = 5000, 5120, 192
     q = binding.query_config(False, M, N, K, 256, K, 256, N, 256, N)
     assert 0 < q["split_rows"] < M
     A, B, C0 = wl.make_inputs(M, N, K, "int1", "zeros", seed=71)
