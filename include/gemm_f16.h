@@ -69,6 +69,16 @@ enum {
  * ((partial sum + C) + rest; on edge tiles it adds C last).  The summation order over
  * k is the kernel's own as well; results are bit-exact wherever every partial
  * sum is exactly representable, and within the f32 rounding bound otherwise.
+ *
+ * Skinny problems (at most half as many 128 x 128 tiles as compute units, K >=
+ * 2048, M*N small) run with the k loop cut into parts: C is not read, every
+ * part adds its sum to the C in memory with hardware f32 atomic additions
+ * (C0 + part + part + ...).  Their order is not fixed, so that two runs may
+ * differ in the last bits (never where the sums are exact), and C must lie in
+ * ordinary device memory (hipMalloc: memory on which the device's
+ * floating-point atomics work).  gemm_f16_query_config reports such a plan by
+ * a grid that is a multiple of the tile count.  The fused form below and the
+ * half-precision mode never run this way.
  */
 int gemm_f16_f32acc(int64_t M, int64_t N, int64_t K,
                     const void* A, int64_t lda,

@@ -119,8 +119,9 @@ bool aligned_for_tiled(int64_t N, int64_t K, const void* A, int64_t lda, const v
 
 // What a call runs: one configuration on all rows, or the 256 x 256 kernel on
 // the first rows1 rows and configuration id2 on the rest (second launch on the
-// same stream; the row ranges of C are disjoint).
-struct Plan { int id; int64_t rows1; int id2; };
+// same stream; the row ranges of C are disjoint); k_split > 1: one launch whose
+// workgroups each take a part of the k loop of a tile.
+struct Plan { int id; int64_t rows1; int id2; int k_split = 0; };
 
 struct Cand { int id; double eff; int per_cu; };
 // The 192- and 128-row forms reuse operands less per tile, but e.g. 6144^3 is exactly three
@@ -275,6 +276,31 @@ Plan select_plan_unchained(int c_is_f16, int64_t M, int64_t N, int64_t K, const 
     return best;
 }
 
+// Few tiles and a long k loop (skinny problems: a few hundred rows, or few columns, against K
+// and the other dimension in the thousands): the time goes into streaming the larger operand,
+// and a compute unit streams at most the bytes it holds in flight per memory latency (about
+// 50 GB/s), so that 64 tiles on 64 compute units reach a fifth of the memory's rate.  In f32
+// mode the k loop is cut so that every compute unit gets a part: workgroups of the five-stage
+// 128 x 128 kernel, one per tile and part of at least 16 k steps (and no more parts than keep
+// the additions under half a million), which add their sums to C with atomic f32 additions (C holds the old C; no fused epilogue, which would have to follow
+// the last part; f16 C would be rounded once per part: both run unsplit).  The order of the
+// additions is not fixed, so results may differ in the last bit from run to run.
+int k_split_if_it_pays(int& id, int c_is_f16, int64_t M, int64_t N, int64_t K)
+{
+    if (c_is_f16 || (id != ID_RING128 && id != ID_PP128x128 && id != ID_T64 && id != ID_PP128)) return 0;
+    const int64_t tiles = config(ID_RING128)->grid(M, N), cus = chip().cus, steps = (K + 63) / 64;
+    if (tiles <= 0 || 2 * tiles > cus) return 0;
+    int64_t parts = cus / tiles < steps / 16 ? cus / tiles : steps / 16;
+    if (parts > 16) parts = 16;
+    // the additions: M x N per part at about 10 us per million (measured: (64,8192,8192) in 4
+    // parts 58 us against 45 unsplit, (512,4096,4096) in 2 parts 67 against 32; (16,8192,8192)
+    // in 4 parts 29 against 47 on the 64 x 64 tiling, (32,4096,4096) in 4 parts 15 against 27)
+    if (parts * M * N > 524288) parts = 524288 / (M * N);
+    if (parts < 2) return 0;
+    id = ID_RING128;
+    return (int)parts;
+}
+
 Plan select_plan(int c_is_f16, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, int64_t ldc)
 {
     Plan pl = select_plan_unchained(c_is_f16, M, N, K, A, lda, B, ldb, ldc);
@@ -283,6 +309,7 @@ Plan select_plan(int c_is_f16, int64_t M, int64_t N, int64_t K, const void* A, i
     pl.id = deep_ring_if_it_pays(pl.id, pl.rows1, N, K);
     if (pl.id2 >= 0) pl.id2 = long_k_if_it_pays(chained_if_it_pays(pl.id2, M - pl.rows1, N, K), c_is_f16, M - pl.rows1, N, K);
     if (pl.id2 >= 0) pl.id2 = deep_ring_if_it_pays(pl.id2, M - pl.rows1, N, K);
+    if (pl.id2 < 0 && pl.rows1 == M) pl.k_split = k_split_if_it_pays(pl.id, c_is_f16, M, N, K);
     return pl;
 }
 
@@ -322,8 +349,10 @@ int run(int c_is_f16, int64_t M, int64_t N, int64_t K, const void* A, int64_t ld
     a.M = plan.rows1; a.N = N; a.K = K;
     a.A = (const half_t*)A; a.lda = lda; a.B = (const half_t*)B; a.ldb = ldb; a.C = C; a.ldc = ldc;
     a.c_is_f16 = c_is_f16; a.stream = (hipStream_t)stream;
+    a.k_split = fused ? 0 : plan.k_split;                   // a fused epilogue has to follow the whole sum
     const int rc1 = config(plan.id)->launch(a);
     if (rc1 != GEMM_F16_OK || plan.rows1 == M) return rc1;
+    a.k_split = 0;
     a.M = M - plan.rows1;                                   // the left-over rows: A and C move down, B stays
     a.A = (const half_t*)A + plan.rows1 * lda;
     a.C = (char*)C + plan.rows1 * ldc * (c_is_f16 ? 2 : 4);
@@ -393,6 +422,7 @@ int gemm_f16_query_config(int c_is_f16, int64_t M, int64_t N, int64_t K, const v
         if (g2 < 0) return GEMM_F16_ERR_SIZE;
         g += g2;
     }
+    if (plan.k_split > 1) g *= plan.k_split;               // one workgroup per tile and part of the k loop
     fill_desc(plan.id, g, out, plan.rows1 < M ? plan.rows1 : 0, plan.rows1 < M ? plan.id2 : -1);
     return GEMM_F16_OK;
 }

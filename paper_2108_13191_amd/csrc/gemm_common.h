@@ -25,6 +25,7 @@ struct GemmArgs {
     hipStream_t stream;
     const void* bias;      // N elements of C's type, or nullptr
     int relu;              // 0 / 1
+    int k_split = 0;       // > 1: the k loop cut into this many parts that add to C atomically (five-stage 128 x 128 kernel, f32 C, no fused epilogue)
 };
 
 // Static description of one kernel configuration.

@@ -19,6 +19,7 @@ struct TiledParams {
     int relu;
     int stagger_ticks;     // late start: workgroups on odd XCDs start this many wall-clock ticks late (0: all at once)
     int first_generation;  // late start: workgroups that begin with the launch (only these wait)
+    int k_split;           // five-stage 128 x 128 kernel: > 1 = workgroup b works on tile b % tiles, part b / tiles of the k loop, and adds to C atomically
 };
 
 // The fields every launcher fills the same way: the problem, the tile grid for bm x bn tiles,

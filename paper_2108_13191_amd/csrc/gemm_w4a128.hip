@@ -49,19 +49,30 @@ __global__ __launch_bounds__(256) void gemm_w4a128_kernel(const TiledParams p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm_base = (wave >> 1) * 64, wn_base = (wave & 1) * 64;
 
+    // Split k (f32 C, no fused epilogue, few tiles and a long k loop: every compute unit should
+    // stream operands): workgroup b takes tile b % tiles and part b / tiles of the k steps, and
+    // adds its sums to C with atomic f32 additions -- C holds the old C already, the order of the
+    // additions is not fixed.  K_len = this workgroup's part of K (all of it without a split).
+    const bool split = p.k_split > 1;
+    const int num_tiles = p.tiles_m * p.tiles_n;
+    const int part = split ? (int)blockIdx.x / num_tiles : 0;
     int tile_m, tile_n;
-    tile_of_block(p, blockIdx.x, tile_m, tile_n);
+    tile_of_block(p, (int)blockIdx.x - part * num_tiles, tile_m, tile_n);
     const int m0 = tile_m * SBM, n0 = tile_n * SBN;
     const bool edge = (m0 + SBM > p.M) || (n0 + SBN > p.N);
 
-    const int kt_full = p.K / BK;
+    const int steps_per_part = split ? ((p.K + BK - 1) / BK + p.k_split - 1) / p.k_split : 0;
+    const int k_begin = part * steps_per_part * BK;
+    if (split && k_begin >= p.K) return;                       // more parts than k steps: nothing to add
+    const int K_len = split ? (p.K - k_begin < steps_per_part * BK ? p.K - k_begin : steps_per_part * BK) : p.K;
+    const int kt_full = K_len / BK;
 
     // ---- copy plan ------------------------------------------------------------------
     // A stage = 16 wave-wide copies of 8 rows x 128 B; wavefront w takes copies q = w + 4t.
     // Lane i writes (row 8q + i/8, chunk position i%8), which holds logical chunk position
     // ^ ((row/2)%8) = 4 (w%2) + i/16, the same for every t.
-    const half_t* const a_tile = p.A + (int64_t)m0 * p.lda;
-    const half_t* const b_tile = p.B + n0;
+    const half_t* const a_tile = p.A + (int64_t)m0 * p.lda + k_begin;
+    const half_t* const b_tile = p.B + (int64_t)k_begin * p.ldb + n0;
     const int a_chunk = (lane & 7) ^ (4 * (wave & 1) + (lane >> 4));
     uint32_t a_off[NCOPY];
 #pragma unroll
@@ -134,6 +145,7 @@ __global__ __launch_bounds__(256) void gemm_w4a128_kernel(const TiledParams p)
     // a group outside C reads the first four elements of the workgroup's tile instead (always
     // inside C) and is not used
     ctx4 cin[4][4];
+    if (!split)
 #pragma unroll
     for (int fm = 0; fm < 4; fm++)
 #pragma unroll
@@ -182,9 +194,9 @@ __global__ __launch_bounds__(256) void gemm_w4a128_kernel(const TiledParams p)
     }
 
     // ---- k tail: one unpipelined step through registers, zero beyond K ------------------
-    if (p.K % BK != 0) {
+    if (K_len % BK != 0) {
         __builtin_amdgcn_s_barrier();                // every wavefront is out of the loop and its copies have landed: stage 0 is free
-        const int k0 = kt_full * BK, krem = p.K - k0;
+        const int k0 = kt_full * BK, krem = K_len - k0;
         const char* a_src = (const char*)(a_tile + k0);
         const char* b_src = (const char*)(b_tile + (int64_t)k0 * p.ldb);
 #pragma unroll
@@ -214,6 +226,22 @@ __global__ __launch_bounds__(256) void gemm_w4a128_kernel(const TiledParams p)
         }
     }
 
+    // ---- split k: this part's sums are added to C (only the launcher's f32 instantiation) ----
+    if constexpr (sizeof(CT) == 4) {
+        if (split) {
+#pragma unroll
+            for (int fm = 0; fm < 4; fm++) {
+                float* const rowp = reinterpret_cast<float*>(reinterpret_cast<char*>(Cbase + (int64_t)(c_row0 + fm * 16) * p.ldc + c_col0) + c_voff);
+#pragma unroll
+                for (int fn = 0; fn < 4; fn++)
+                    if (c_ok(fm, fn)) {
+#pragma unroll
+                        for (int e = 0; e < 4; e++) unsafeAtomicAdd(rowp + fn * 16 + e, acc[fm][fn][e]);
+                    }
+            }
+            return;
+        }
+    }
     // ---- + C, + bias, ReLU, -> C ------------------------------------------------------
 #pragma unroll
     for (int fm = 0; fm < 4; fm++) {
@@ -240,11 +268,15 @@ int launch_w4a128(const GemmArgs& a)
 {
     const int64_t g = grid_w4a128(a.M, a.N);
     if (g < 0) return GEMM_F16_ERR_SIZE;
-    const TiledParams p = make_tiled_params(a, SBM, SBN, 8);   // an XCD's 64 concurrent tiles form an 8 x 8 block of C
+    TiledParams p = make_tiled_params(a, SBM, SBN, 8);   // an XCD's 64 concurrent tiles form an 8 x 8 block of C
+    // the parts of a split k loop add to C atomically: f32 C and no bias or activation, which would have to wait for the last part
+    const int parts = (a.k_split > 1 && !a.c_is_f16 && !a.bias && !a.relu) ? a.k_split : 1;
+    if (g * parts > INT32_MAX) return GEMM_F16_ERR_SIZE;
+    p.k_split = parts;
     if (a.c_is_f16)
         hipLaunchKernelGGL(gemm_w4a128_kernel<half_t>, dim3((unsigned)g), dim3(256), 0, a.stream, p);
     else
-        hipLaunchKernelGGL(gemm_w4a128_kernel<float>, dim3((unsigned)g), dim3(256), 0, a.stream, p);
+        hipLaunchKernelGGL(gemm_w4a128_kernel<float>, dim3((unsigned)(g * parts)), dim3(256), 0, a.stream, p);
     return hipGetLastError() == hipSuccess ? GEMM_F16_OK : GEMM_F16_ERR_LAUNCH;
 }
 

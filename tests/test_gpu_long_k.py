@@ -116,3 +116,38 @@ def test_five_stage_kernel_selected_for_few_tiles_and_a_long_k_loop(oracle_mod):
         assert binding.query_config(0, 2048, 2048, k, 16, k, 16, 2048, 16, 2048)["name"].startswith("pp128x128")
     assert binding.query_config(0, 2048, 4096, 8192, 16, 8192, 16, 4096, 16, 4096)["name"] != NAME128
     assert binding.query_config(0, 256, 7168, 7168, 16, 7168, 16, 7168, 16, 7168)["name"] == NAME128      # a strip of 112 tiles
+
+
+def test_split_k_plans_of_skinny_problems(oracle_mod):
+    """Few 128 x 128 tiles and a long k loop, f32 mode: the k loop is cut into parts of at least
+    16 k steps (as many as keep the additions under half a million), one workgroup of the
+    five-stage kernel per tile and part, which add to C atomically.  Integers bit for bit (any order of exact additions), random data to tolerance,
+    with a k tail, ragged edges, a C pitch that is not N; the same problems in f16 mode and
+    with a fused epilogue run unsplit."""
+    from gpu_util import DevMat
+    cases = [((16, 1024, 2048), 2), ((100, 520, 4096 + 24), 4), ((300, 264, 8192), 6), ((16, 8192, 8192), 4), ((256, 512, 16384 + 8), 4)]
+    for idx, ((M, N, K), parts) in enumerate(cases):
+        tiles = ((M + 127) // 128) * ((N + 127) // 128)
+        q = binding.query_config(False, M, N, K, 16, K, 16, N, 16, N + 8 * idx)
+        assert q["name"] == NAME128 and q["grid"] == tiles * parts, (M, N, K, q)
+        assert binding.query_config(True, M, N, K, 16, K, 16, N, 16, N)["grid"] <= max(tiles, ((M + 63) // 64) * ((N + 63) // 64))
+        A, B, _ = wl.make_inputs(M, N, K, "int2", "zeros", seed=1100 + idx)
+        C0 = np.random.default_rng(idx).integers(-4, 5, size=(M, N)).astype(np.float32)
+        got = run_gemm(A, B, C0, "f32", ldc=N + 8 * idx)
+        Cref, _ = oracle_mod.gemm_f16(A, B, C0)
+        assert np.array_equal(got, oracle_mod.round_to_f32(Cref)), f"ints {(M, N, K)}"
+        for mode in ("f32", "f16"):
+            A, B, C0 = wl.make_inputs(M, N, K, "uniform", "uniform", seed=1110 + idx, c_dtype=CDT[mode])
+            got = run_gemm(A, B, C0, mode, ldc=N + 8 * idx)
+            Cref, S = oracle_mod.gemm_f16(A, B, C0)
+            assert_close(got, Cref, S, C0, mode, what=f"split k {(M, N, K)} {mode}")
+    # a fused epilogue on such a problem: one pass over k, bias and ReLU behind it
+    M, N, K = 100, 520, 4096
+    A, B, _ = wl.make_inputs(M, N, K, "int2", "zeros", seed=1150)
+    C0 = np.random.default_rng(5).integers(-4, 5, size=(M, N)).astype(np.float32)
+    bias = (np.arange(N) % 7 - 3).astype(np.float32)
+    dA, dB, dC, dbias = DevMat(A, nan_canary=True), DevMat(B, nan_canary=True), DevMat(C0), torch.from_numpy(bias).cuda()
+    binding.check(binding.gemm_f16_f32acc_bias_act(M, N, K, dA.ptr, dA.ld, dB.ptr, dB.ld, dC.ptr, dC.ld, dbias, binding.ACT_RELU, 0))
+    torch.cuda.synchronize()
+    Cref, _ = oracle_mod.gemm_f16(A, B, C0)
+    assert np.array_equal(dC.fetch(), np.maximum(oracle_mod.round_to_f32(Cref) + bias[None, :], 0).astype(np.float32))
