@@ -282,7 +282,7 @@ Plan select_plan_unchained(int c_is_f16, int64_t M, int64_t N, int64_t K, const 
 // 50 GB/s), so that 64 tiles on 64 compute units reach a fifth of the memory's rate.  In f32
 // mode the k loop is cut so that every compute unit gets a part: workgroups of the five-stage
 // 128 x 128 kernel, one per tile and part of at least 16 k steps (and no more parts than keep
-// the additions under half a million), which add their sums to C with atomic f32 additions (C holds the old C; no fused epilogue, which would have to follow
+// the additions under four million), which add their sums to C with atomic f32 additions (C holds the old C; no fused epilogue, which would have to follow
 // the last part; f16 C would be rounded once per part: both run unsplit).  The order of the
 // additions is not fixed, so results may differ in the last bit from run to run.
 int k_split_if_it_pays(int& id, int c_is_f16, int64_t M, int64_t N, int64_t K)
@@ -292,10 +292,11 @@ int k_split_if_it_pays(int& id, int c_is_f16, int64_t M, int64_t N, int64_t K)
     if (tiles <= 0 || 2 * tiles > cus) return 0;
     int64_t parts = cus / tiles < steps / 16 ? cus / tiles : steps / 16;
     if (parts > 16) parts = 16;
-    // the additions: M x N per part at about 10 us per million (measured: (64,8192,8192) in 4
-    // parts 58 us against 45 unsplit, (512,4096,4096) in 2 parts 67 against 32; (16,8192,8192)
-    // in 4 parts 29 against 47 on the 64 x 64 tiling, (32,4096,4096) in 4 parts 15 against 27)
-    if (parts * M * N > 524288) parts = 524288 / (M * N);
+    // the additions: M x N per part, a row of 64 floats per instruction, about 5 us per million;
+    // measured with at most 4 million of them (before -> after): (64,8192,8192) 49 -> 30 us,
+    // (128,8192,8192) 52 -> 37, (256,8192,8192) 54 -> 45, (1024,2048,8192) 57 -> 47,
+    // (512,4096,4096) 31 -> 32
+    if (parts * M * N > 4194304) parts = 4194304 / (M * N);
     if (parts < 2) return 0;
     id = ID_RING128;
     return (int)parts;

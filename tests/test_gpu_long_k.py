@@ -120,12 +120,12 @@ def test_five_stage_kernel_selected_for_few_tiles_and_a_long_k_loop(oracle_mod):
 
 def test_split_k_plans_of_skinny_problems(oracle_mod):
     """Few 128 x 128 tiles and a long k loop, f32 mode: the k loop is cut into parts of at least
-    16 k steps (as many as keep the additions under half a million), one workgroup of the
+    16 k steps (as many as keep the additions under four million), one workgroup of the
     five-stage kernel per tile and part, which add to C atomically.  Integers bit for bit (any order of exact additions), random data to tolerance,
     with a k tail, ragged edges, a C pitch that is not N; the same problems in f16 mode and
     with a fused epilogue run unsplit."""
     from gpu_util import DevMat
-    cases = [((16, 1024, 2048), 2), ((100, 520, 4096 + 24), 4), ((300, 264, 8192), 6), ((16, 8192, 8192), 4), ((256, 512, 16384 + 8), 4)]
+    cases = [((16, 1024, 2048), 2), ((100, 520, 4096 + 24), 4), ((300, 264, 8192), 8), ((64, 8192, 8192), 4), ((256, 512, 16384 + 8), 16)]
     for idx, ((M, N, K), parts) in enumerate(cases):
         tiles = ((M + 127) // 128) * ((N + 127) // 128)
         q = binding.query_config(False, M, N, K, 16, K, 16, N, 16, N + 8 * idx)
