@@ -20,6 +20,9 @@ WORKLOADS = {
     "ffn_down":         (16384, 768, 3072, "normal_0p02", "zeros", ("f32",)),
     "qkv":              (16384, 2304, 768, "normal_0p02", "zeros", ("f32",)),
     "ragged4000":       (4000, 4000, 4000, "normal_0p02", "zeros", ("f32",)),
+    # skinny: a few rows against a large weight matrix (bound by streaming B)
+    "skinny16":         (16, 8192, 8192, "normal_0p02", "zeros", ("f32", "f16")),
+    "skinny256":        (256, 4096, 16384, "normal_0p02", "zeros", ("f32", "f16")),
 }
 SQUARE_SWEEP = tuple(range(1024, 16384 + 1, 1024))  # uniform A, B; C0 zero; both modes
 
