@@ -8,10 +8,12 @@
 // back, with the 24 LDS reads and 8 copies of the step in their shadow and one barrier
 // (gemm_w4a128_loop.inc, written by gen_w4a128_loop.py).
 //
-// C is read before the loop (into registers), added and stored behind it.  A k tail (K % 64 != 0) is one unpipelined step
-// through registers after the loop.  Requirements as for the other tuned kernels: A, B 16-byte
-// aligned; lda, ldb, K, N multiples of 8.  Rows >= M / columns >= N are fetched from clamped
-// addresses and never stored.
+// C is read before the loop (into registers), added and stored behind it.  A k tail (K % 64
+// != 0) is one unpipelined step through registers after the loop.  With a split k loop (skinny
+// f32 problems) a workgroup multiplies a part of the k steps of its tile and adds the result to
+// C atomically instead.  Requirements as for the other tuned kernels: A, B 16-byte aligned;
+// lda, ldb, K, N multiples of 8.  Rows >= M / columns >= N are fetched from clamped addresses
+// and never stored.
 #include "gemm_device.h"
 #include "../../include/gemm_f16.h"
 #include "gemm_w4a128_loop.inc"
@@ -61,9 +63,10 @@ __global__ __launch_bounds__(256) void gemm_w4a128_kernel(const TiledParams p)
     const int m0 = tile_m * SBM, n0 = tile_n * SBN;
     const bool edge = (m0 + SBM > p.M) || (n0 + SBN > p.N);
 
-    const int steps_per_part = split ? ((p.K + BK - 1) / BK + p.k_split - 1) / p.k_split : 0;
-    const int k_begin = part * steps_per_part * BK;
-    if (split && k_begin >= p.K) return;                       // more parts than k steps: nothing to add
+    const int k_steps = p.K / BK + (p.K % BK != 0);
+    const int steps_per_part = split ? (k_steps + p.k_split - 1) / p.k_split : 0;
+    if (split && part * steps_per_part >= k_steps) return;     // more parts than k steps: nothing to add
+    const int k_begin = part * steps_per_part * BK;            // < K
     const int K_len = split ? (p.K - k_begin < steps_per_part * BK ? p.K - k_begin : steps_per_part * BK) : p.K;
     const int kt_full = K_len / BK;
 

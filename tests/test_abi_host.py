@@ -195,3 +195,26 @@ def test_plan_invariants_on_random_shapes(lib):
         if q["name"].endswith("_stag"):
             assert K <= 1024 and tiles256 >= 512 and 0 < tiles256 % 256 <= 128 and q["grid"] == tiles256 + 128
         assert q["id"] < n_product                                                   # comparison kernels are never selected
+
+
+def test_split_k_plan_invariants(lib):
+    """The k loop is cut only in f32 mode, only for the five-stage 128 x 128 kernel, into parts
+    of at least 16 k steps, with at most one workgroup per compute unit and at most four million
+    additions; the f16 query of the same shape never reports it."""
+    rng = np.random.default_rng(777)
+    seen = 0
+    for _ in range(3000):
+        M = int(rng.integers(1, 600))
+        N = int(rng.integers(1, 1200)) * 8
+        K = int(rng.integers(16, 4000)) * 8
+        tiles = ((M + 127) // 128) * ((N + 127) // 128)
+        q = binding.query_config(0, M, N, K, 256, K, 256, N, 256, N)
+        q16 = binding.query_config(1, M, N, K, 256, K, 256, N, 256, N)
+        if q["name"] == "w4a_128x128x64" and q["grid"] != tiles:
+            parts = q["grid"] // tiles
+            assert q["grid"] == parts * tiles and 2 <= parts <= 16 and q["grid"] <= 256 and not q["split_rows"], (M, N, K, q)
+            assert parts * M * N <= 4194304 and (K + 63) // 64 >= 16 * parts, (M, N, K, q)
+            seen += 1
+        if q16["name"] == "w4a_128x128x64":
+            assert q16["grid"] == tiles, (M, N, K, q16)
+    assert seen > 300
