@@ -217,12 +217,14 @@ def test_two_streams_concurrently(oracle_mod):
         assert np.array_equal(dC.fetch(), oracle_mod.round_to_f32(3.0 * Cref))      # integer data: exact
 
 
-def test_under_hip_graph_capture(oracle_mod):
+@pytest.mark.parametrize("shape", [(1024, 1032, 520), (72, 520, 4096)])
+def test_under_hip_graph_capture(oracle_mod, shape):
     """The entry points only enqueue kernels (no allocation, no synchronisation,
     no memset), so a call can be captured into a HIP graph; every replay, with
-    eager work and synchronisations in between, must equal the eager result."""
+    eager work and synchronisations in between, must equal the eager result.  The second
+    shape runs with its k loop cut into parts that add to C atomically."""
     from gpu_util import DevMat
-    M, N, K = 1024, 1032, 520
+    M, N, K = shape
     A, B, C0 = wl.make_inputs(M, N, K, "int2", "zeros", seed=50)
     dA, dB, dC = DevMat(A, nan_canary=True), DevMat(B, nan_canary=True), DevMat(C0)
     Cref, _ = oracle_mod.gemm_f16(A, B, C0)
