@@ -354,9 +354,14 @@ __device__ __forceinline__ void pp_tile(const TiledParams& p, const uint32_t sme
             for (int fm = 0; fm < FM; fm++)
 #pragma unroll
                 for (int fn = 0; fn < FN; fn++) {
-                    // B fragment first: the transposed block
-                    if constexpr (MI == 32) acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[s][fn], fa[s][fm], acc[fm][fn], 0, 0, 0);
-                    else                    acc[fm][fn] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fb[s][fn], fa[s][fm], acc[fm][fn], 0, 0, 0);
+                    // B fragment first: the transposed block.  The blocks of a slice are walked
+                    // in serpentine order (rows of blocks left to right, then right to left), so
+                    // that from one MFMA to the next exactly one of the two operands changes:
+                    // with both changing at every row end (7 of 32 steps) the part, which is at
+                    // its power limit, ran 1 % (f32 C) to 1.6 % (f16 C) slower on the headline.
+                    const int gm = fm, gn = (fm & 1) ? FN - 1 - fn : fn;
+                    if constexpr (MI == 32) acc[gm][gn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[s][gn], fa[s][gm], acc[gm][gn], 0, 0, 0);
+                    else                    acc[gm][gn] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fb[s][gn], fa[s][gm], acc[gm][gn], 0, 0, 0);
                     const int idx = (s * FM + fm) * FN + fn;
                     if constexpr (decltype(copy_tag)::value == 1) {
                         // whole k step: copy t is loaded behind MFMA t * NMFMA/4 + NMFMA/8 - 1 and its M0 is

@@ -62,7 +62,8 @@ def acc(fm, fn):
 
 
 def mfma(d, i):
-    fm, fn = i // FN, i % FN
+    fm = i // FN
+    fn = i % FN if fm % 2 == 0 else FN - 1 - i % FN       # serpentine: one operand changes per MFMA (see gen_w4a_loop.block_at)
     return f"v_mfma_f32_16x16x32_f16 {acc(fm, fn)}, {frag_b(d, fn)}, {frag_a(d, fm)}, {acc(fm, fn)}"
 
 

@@ -89,8 +89,22 @@ def acc(fm, fn):
     return f"a[{lo}:{lo + 3}]"
 
 
+def block_at(i):
+    """(fm, fn) of MFMA i of a slice: the rows of blocks in serpentine order, so that from one MFMA
+    to the next exactly one of the two operands changes (with both changing at every row end the
+    part, which runs at its power limit, is about 1 % slower)."""
+    fm = i >> 3
+    return fm, (i & 7) if fm % 2 == 0 else 7 - (i & 7)
+
+
+def slot_of(b):
+    """The MFMA of a slice that works on block b = 8 fm + fn."""
+    fm, fn = b >> 3, b & 7
+    return 8 * fm + (fn if fm % 2 == 0 else 7 - fn)
+
+
 def mfma(d, i):
-    fm, fn = i >> 3, i & 7
+    fm, fn = block_at(i)
     return f"v_mfma_f32_16x16x32_f16 {acc(fm, fn)}, {frag_b(d, fn)}, {frag_a(d, fm)}, {acc(fm, fn)}"
 
 
@@ -125,12 +139,12 @@ CLEAN_SLOTS = [i for i in range(63) if (i < 48 and i % 8 in (0, 2)) or (i >= 48 
 def add_plan(blocks):
     """slot -> instructions that add the loaded C blocks (block, first register of its C data) to
     their accumulators, one accumulator register per slot: read it, add, write it back.  The
-    MFMA of block b is number b of every slice of 64: a slot qualifies for b if the last such
-    MFMA was issued at least 6 MFMAs before it (its result is there) and the next one comes at
-    least 3 MFMAs after it (the write is seen)."""
+    MFMA of block b is number slot_of(b) of every slice of 64: a slot qualifies for b if the last
+    such MFMA was issued at least 6 MFMAs before it (its result is there) and the next one comes
+    at least 3 MFMAs after it (the write is seen)."""
     plan, free = {}, list(CLEAN_SLOTS)
     for b, reg in blocks:
-        ok = [s for s in free if (s - b) % 64 >= 6 and (b - s) % 64 >= 3]
+        ok = [s for s in free if (s - slot_of(b)) % 64 >= 6 and (slot_of(b) - s) % 64 >= 3]
         assert len(ok) >= 4, (b, free)
         for e, s in enumerate(ok[:4]):
             free.remove(s)

@@ -158,6 +158,14 @@ def test_scalar_side_of_the_loop_for_every_trip_count(name, with_c):
         trace, nmfma = _run(lines, kt, AHEAD)
         _check_c(gen, trace, with_c)
         assert nmfma == 2 * SL * kt
+        # every slice multiplies every block of the wavefront's tile once, and from one MFMA of a
+        # slice to the next exactly one operand changes (same block row or same block column)
+        order = [e[2] for e in trace if e[1] == "mfma"]
+        width = 8 if SL == 64 else 4
+        for i in range(0, len(order), SL):
+            assert sorted(order[i:i + SL]) == list(range(SL)), ("blocks of a slice", kt, i // SL)
+            for a, b in zip(order[i:i + SL - 1], order[i + 1:i + SL]):
+                assert (a // width == b // width) != (a % width == b % width), ("both operands change", a, b)
         barriers = [e[0] for e in trace if e[1] == "barrier"]
         assert len(barriers) == kt
         # --- copies: (time, buffer, k step), where they come from and where they land
