@@ -176,7 +176,8 @@ def ceiling_result(launches, cus):
     flops = float(cus) * 8 * iters * 32 * 16384
     return {"value": round(flops / (ms * 1e-3) / 1e12, 1), "unit": "TFLOP/s", "ms": round(ms, 3),
             "frac_of_peak": round(flops / (ms * 1e-3) / 1e12 / PEAK_F16_MFMA_TFLOPS, 4),
-            "what": "v_mfma_f32_16x16x32_f16 only, two wavefronts per SIMD, 8 x 4 accumulator blocks per wavefront, "
+            "what": "v_mfma_f32_16x16x32_f16 only, two wavefronts per SIMD, 8 x 4 accumulator blocks per wavefront "
+                    "walked in the library's order (one operand changes per MFMA), "
                     "operands in registers drawn from the workload's distribution; last of three back-to-back launches"}
 
 

@@ -29,7 +29,7 @@ Run: python3 gen_w4a128_loop.py   (writes gemm_w4a128_loop.inc beside itself)
 """
 import os
 
-from gen_w4a_loop import S_J, S_J2, S_ASRC, S_BSRC, S_APTR, S_BPTR, asm_macro
+from gen_w4a_loop import S_J, S_J2, S_ASRC, S_BSRC, S_APTR, S_BPTR, asm_macro, snake
 
 A_BUF = 16384
 B_BUF = 16384
@@ -62,8 +62,7 @@ def acc(fm, fn):
 
 
 def mfma(d, i):
-    fm = i // FN
-    fn = i % FN if fm % 2 == 0 else FN - 1 - i % FN       # serpentine: one operand changes per MFMA (see gen_w4a_loop.block_at)
+    fm, fn = snake(i, FN)                                 # one operand changes per MFMA, A back and forth between two
     return f"v_mfma_f32_16x16x32_f16 {acc(fm, fn)}, {frag_b(d, fn)}, {frag_a(d, fm)}, {acc(fm, fn)}"
 
 
