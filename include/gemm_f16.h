@@ -132,6 +132,33 @@ int gemm_f16_f16acc_bias_act(int64_t M, int64_t N, int64_t K,
                              const void* bias, int act,
                              void* stream);
 
+/*
+ * The half-precision mode for callers that can lend scratch memory (paper,
+ * section Half Precision Performance; same result as gemm_f16_f16acc to the
+ * bound of the mode).  Skinny problems -- few 128 x 128 tiles, a long k loop:
+ * the shapes gemm_f16_f32acc cuts along k -- are bound by how fast one compute
+ * unit per tile can stream the larger operand.  With a workspace of M*N
+ * floats the k loop is cut into parts here too: the workspace is zeroed, the
+ * parts add their f32 sums to it atomically, and a last pass stores
+ * round(C + workspace) to C, the mode's one rounding (three launches on the
+ * caller's stream; (16,8192,8192): 29 us against 49 unsplit, (128,128,8192):
+ * 15 against 49; problems of more than 2^20 results run unsplit).
+ * gemm_f16_f16acc_workspace_bytes returns the bytes that make a difference
+ * for a problem (0: it would run as gemm_f16_f16acc anyway; sizes only, for
+ * 16-byte aligned operands with dense rows).  workspace: device memory,
+ * 16-byte aligned (else GEMM_F16_ERR_ALIGN), owned by the caller, used only
+ * between the call and the completion of its work on the stream, contents
+ * undefined afterwards; NULL or too small: the call runs unsplit.  Two calls
+ * may share a workspace only if they are ordered on one stream.
+ */
+int64_t gemm_f16_f16acc_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int gemm_f16_f16acc_workspace(int64_t M, int64_t N, int64_t K,
+                              const void* A, int64_t lda,
+                              const void* B, int64_t ldb,
+                              void* C, int64_t ldc,
+                              void* workspace, int64_t workspace_bytes,
+                              void* stream);
+
 /* Static, human-readable text for a return code. Never NULL. */
 const char* gemm_strerror(int code);
 

@@ -73,6 +73,10 @@ def load() -> ctypes.CDLL:
             f = getattr(lib, name)
             f.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, ci, vp]
             f.restype = ci
+        lib.gemm_f16_f16acc_workspace_bytes.argtypes = [i64, i64, i64]
+        lib.gemm_f16_f16acc_workspace_bytes.restype = i64
+        lib.gemm_f16_f16acc_workspace.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, i64, vp]
+        lib.gemm_f16_f16acc_workspace.restype = ci
         lib.gemm_strerror.argtypes = [ci]
         lib.gemm_strerror.restype = ctypes.c_char_p
         lib.gemm_f16_query_config.argtypes = [ci, i64, i64, i64, vp, i64, vp, i64, vp, i64,
@@ -104,6 +108,16 @@ def gemm_f16_f32acc(M, N, K, A, lda, B, ldb, C, ldc, stream=0) -> int:
 def gemm_f16_f16acc(M, N, K, A, lda, B, ldb, C, ldc, stream=0) -> int:
     """C (f16) += A (f16) @ B (f16), f32 accumulation, one rounding on store."""
     return load().gemm_f16_f16acc(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, _ptr(stream))
+
+
+def gemm_f16_f16acc_workspace_bytes(M, N, K) -> int:
+    """Bytes of workspace that let gemm_f16_f16acc_workspace cut this problem along k (0: none needed)."""
+    return load().gemm_f16_f16acc_workspace_bytes(M, N, K)
+
+
+def gemm_f16_f16acc_workspace(M, N, K, A, lda, B, ldb, C, ldc, workspace, workspace_bytes, stream=0) -> int:
+    """gemm_f16_f16acc with caller-provided scratch memory (device, 16-byte aligned) for split-k plans."""
+    return load().gemm_f16_f16acc_workspace(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, _ptr(workspace), workspace_bytes, _ptr(stream))
 
 
 ACT_NONE, ACT_RELU = 0, 1

@@ -18,7 +18,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgemm_f16.so")
 LADDER_LIB = os.path.join(HERE, "libgemm_f16_ladder.so")
-SOURCES = ["gemm_api.hip", "gemm_generic.hip", "gemm_tiled.hip", "gemm_pingpong.hip", "gemm_w4a.hip", "gemm_w4a128.hip"]
+SOURCES = ["gemm_api.hip", "gemm_generic.hip", "gemm_tiled.hip", "gemm_pingpong.hip", "gemm_w4a.hip", "gemm_w4a128.hip", "gemm_splitk_f16.hip"]
 LADDER_SOURCES = ["ladder/gemm_w4.hip", "ladder/gemm_overlap.hip", "ladder/gemm_interleaved.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
          # packed-f32 VALU forms are kept off for every HIP file of this library

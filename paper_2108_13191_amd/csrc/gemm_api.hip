@@ -360,9 +360,56 @@ int run(int c_is_f16, int64_t M, int64_t N, int64_t K, const void* A, int64_t ld
     return config(plan.id2)->launch(a);
 }
 
+// Parts of a split k loop for the half-precision mode through a workspace (0: runs unsplit):
+// the rule of the f32 mode on the plan the f16 mode would take.
+int f16_workspace_parts(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb, int64_t ldc)
+{
+    if (M <= 0 || N <= 0 || K <= 0 || !aligned_for_tiled(N, K, A, lda, B, ldb, ldc) || (g_forced >= 0 && g_forced < num_configs())) return 0;
+    const Plan pl = select_plan(1, M, N, K, A, lda, B, ldb, ldc);
+    if (pl.id2 >= 0 || pl.rows1 != M) return 0;
+    // the two passes over the workspace: (1024,2048,8192), 8 MB, 56 us against 53 unsplit; (256,4096,16384), 4 MB, 52 against 97
+    if (M * N > 1048576) return 0;
+    int id = pl.id;
+    return k_split_if_it_pays(id, 0, M, N, K);
+}
+
+// The half-precision mode with `ws` (M x N floats, 16-byte aligned, all zero if ws_is_zero) as the
+// f32 sum of the parts; clear_after: leave it all zero again.
+int run_f16_split(int parts, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B, int64_t ldb,
+                  void* C, int64_t ldc, float* ws, bool ws_is_zero, bool clear_after, void* stream)
+{
+    int rc = ws_is_zero ? GEMM_F16_OK : splitk_f16_zero(ws, M * N, (hipStream_t)stream);   // N is a multiple of 8
+    if (rc != GEMM_F16_OK) return rc;
+    GemmArgs a;
+    a.M = M; a.N = N; a.K = K;
+    a.A = (const half_t*)A; a.lda = lda; a.B = (const half_t*)B; a.ldb = ldb; a.C = ws; a.ldc = N;
+    a.c_is_f16 = 0; a.stream = (hipStream_t)stream; a.bias = nullptr; a.relu = 0; a.k_split = parts;
+    rc = config(ID_RING128)->launch(a);
+    if (rc != GEMM_F16_OK) return rc;
+    return splitk_f16_finish(ws, C, ldc, M, N, clear_after ? 1 : 0, (hipStream_t)stream);
+}
+
 }  // namespace
 
 extern "C" {
+
+int64_t gemm_f16_f16acc_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    if (M <= 0 || N <= 0 || K <= 0 || M > INT32_MAX || N > INT32_MAX || K > INT32_MAX) return 0;
+    return f16_workspace_parts(M, N, K, (const void*)16, K, (const void*)16, N, N) >= 2 ? M * N * 4 : 0;
+}
+
+int gemm_f16_f16acc_workspace(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                              const void* B, int64_t ldb, void* C, int64_t ldc,
+                              void* workspace, int64_t workspace_bytes, void* stream)
+{
+    const int rc = check_args(1, M, N, K, A, lda, B, ldb, C, ldc);
+    if (rc != GEMM_F16_OK) return rc;
+    if (workspace && ((uintptr_t)workspace & 15)) return GEMM_F16_ERR_ALIGN;
+    const int parts = f16_workspace_parts(M, N, K, A, lda, B, ldb, ldc);
+    if (parts < 2 || !workspace || workspace_bytes < M * N * 4) return run(1, M, N, K, A, lda, B, ldb, C, ldc, stream);
+    return run_f16_split(parts, M, N, K, A, lda, B, ldb, C, ldc, (float*)workspace, false, false, stream);
+}
 
 int gemm_f16_f32acc(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
                     const void* B, int64_t ldb, float* C, int64_t ldc, void* stream)

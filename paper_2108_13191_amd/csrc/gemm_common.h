@@ -66,6 +66,10 @@ const GemmConfigDesc* long_k_config();                                // 256x256
 // gemm_w4a128.hip
 const GemmConfigDesc* deep_ring_config();                             // 128x128, four wavefronts of 64x64, k loop in assembly over five LDS stages
 
+// gemm_splitk_f16.hip: the passes around a split-k launch in the half-precision mode
+int splitk_f16_zero(float* ws, int64_t n, hipStream_t stream);
+int splitk_f16_finish(float* ws, void* C, int64_t ldc, int64_t M, int64_t N, int clear, hipStream_t stream);
+
 #ifdef GEMM_F16_LADDER
 // Comparison kernels and ablation rows: built into libgemm_f16_ladder.so only, never selected.
 const GemmConfigDesc* pingpong_config();                             // gemm_pingpong.hip: 256x256 on 32x32x16 MFMAs

@@ -151,3 +151,40 @@ def test_split_k_plans_of_skinny_problems(oracle_mod):
     torch.cuda.synchronize()
     Cref, _ = oracle_mod.gemm_f16(A, B, C0)
     assert np.array_equal(dC.fetch(), np.maximum(oracle_mod.round_to_f32(Cref) + bias[None, :], 0).astype(np.float32))
+
+
+def test_half_precision_mode_with_a_workspace(oracle_mod):
+    """gemm_f16_f16acc_workspace: with M x N floats of scratch memory the skinny problems that the
+    f32 mode cuts along k are cut in the f16 mode too (the parts add to the zeroed workspace, a last
+    pass rounds C + workspace once).  Integers bit for bit against the oracle's one rounding, random
+    data to the mode's tolerance, a C pitch that is not N, a workspace that holds garbage before;
+    without a workspace, or with one that is too small, the call runs unsplit with the same result."""
+    from gpu_util import DevMat
+    cases = [(16, 1024, 2048), (100, 520, 4096 + 24), (300, 264, 8192), (64, 2048, 4096)]
+    for idx, (M, N, K) in enumerate(cases):
+        need = binding.gemm_f16_f16acc_workspace_bytes(M, N, K)
+        assert need == M * N * 4, (M, N, K, need)
+        ws = torch.full((need // 4 + 4,), float("nan"), device="cuda")
+        for dist, exact in (("int2", True), ("uniform", False)):
+            A, B, C0 = wl.make_inputs(M, N, K, dist, "zeros" if exact else "uniform", seed=1200 + idx, c_dtype=np.float16)
+            if exact:
+                C0 = np.random.default_rng(idx).integers(-4, 5, size=(M, N)).astype(np.float16)
+            Cref, S = oracle_mod.gemm_f16(A, B, C0)
+            for ws_bytes in (need, need - 4, 0):
+                dA, dB, dC = DevMat(A, nan_canary=True), DevMat(B, nan_canary=True), DevMat(C0, N + 8 * idx, 1)
+                ws.fill_(float("nan"))
+                binding.check(binding.gemm_f16_f16acc_workspace(M, N, K, dA.ptr, dA.ld, dB.ptr, dB.ld, dC.ptr, dC.ld,
+                                                                ws if ws_bytes else 0, ws_bytes, 0))
+                torch.cuda.synchronize()
+                got = dC.fetch()
+                if exact:
+                    assert np.array_equal(got, Cref.astype(np.float16)), f"ints {(M, N, K)} workspace {ws_bytes}"
+                else:
+                    assert_close(got, Cref, S, C0, "f16", what=f"workspace {(M, N, K)} {ws_bytes}")
+    # nothing to gain: no workspace asked for, and a workspace changes nothing
+    assert binding.gemm_f16_f16acc_workspace_bytes(4096, 4096, 4096) == 0
+    assert binding.gemm_f16_f16acc_workspace_bytes(16, 1024, 512) == 0
+    ws = torch.zeros(64, device="cuda")
+    A, B, C0 = wl.make_inputs(64, 64, 64, "int2", "zeros", seed=3, c_dtype=np.float16)
+    dA, dB, dC = DevMat(A), DevMat(B), DevMat(C0)
+    assert binding.gemm_f16_f16acc_workspace(64, 64, 64, dA.ptr, 64, dB.ptr, 64, dC.ptr, 64, ws.data_ptr() + 4, 252, 0) == binding.ERR_ALIGN
