@@ -52,7 +52,8 @@ enum {
     GEMM_F16_ERR_NULL = -3,    /* a needed pointer is NULL */
     GEMM_F16_ERR_LAUNCH = -4,  /* the HIP runtime refused the launch */
     GEMM_F16_ERR_CONFIG = -5,  /* unknown configuration id / bad query argument */
-    GEMM_F16_ERR_ALIGN = -6    /* C is not aligned to its element size, or A/B to 2 bytes */
+    GEMM_F16_ERR_ALIGN = -6,   /* C is not aligned to its element size, or A/B to 2 bytes */
+    GEMM_F16_ERR_WORKSPACE = -7 /* gemm_f16_f16acc_static_workspace: more scratch memory needed than the library holds */
 };
 
 /*
@@ -158,6 +159,27 @@ int gemm_f16_f16acc_workspace(int64_t M, int64_t N, int64_t K,
                               void* C, int64_t ldc,
                               void* workspace, int64_t workspace_bytes,
                               void* stream);
+
+/*
+ * gemm_f16_f16acc_workspace for callers that cannot allocate device memory and
+ * have none to lend: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid allocation.  The scratch memory is the library's own,
+ * a fixed array of 2^20 floats (4 MB) in the library's device image on every
+ * GPU it runs on, held until the process ends; the call allocates and frees
+ * nothing and records no memset (the array is cleared by a small kernel).  A
+ * problem whose split plan needs more than the array holds is rejected with
+ * GEMM_F16_ERR_WORKSPACE (as the selector stands no plan does); problems that
+ * run unsplit do not touch the array.  Every call on a GPU uses that GPU's one
+ * array: calls that can overlap on one GPU (two streams, two threads) race
+ * and must be ordered by the caller; gemm_f16_f16acc has no such restriction.
+ * The array's address is looked up at the first call on a device (not a
+ * stream operation): make that call outside a graph capture.
+ */
+int gemm_f16_f16acc_static_workspace(int64_t M, int64_t N, int64_t K,
+                                     const void* A, int64_t lda,
+                                     const void* B, int64_t ldb,
+                                     void* C, int64_t ldc,
+                                     void* stream);
 
 /* Static, human-readable text for a return code. Never NULL. */
 const char* gemm_strerror(int code);

@@ -34,7 +34,7 @@ def library(kind: str):
         _active = prev
 
 OK = 0
-ERR_SIZE, ERR_PITCH, ERR_NULL, ERR_LAUNCH, ERR_CONFIG, ERR_ALIGN = -1, -2, -3, -4, -5, -6
+ERR_SIZE, ERR_PITCH, ERR_NULL, ERR_LAUNCH, ERR_CONFIG, ERR_ALIGN, ERR_WORKSPACE = -1, -2, -3, -4, -5, -6, -7
 
 
 class GemmConfig(ctypes.Structure):
@@ -65,7 +65,7 @@ def load() -> ctypes.CDLL:
                 "(python -m paper_2108_13191_amd.build); there is no CPU fallback")
         lib = ctypes.CDLL(path)
         i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
-        for name in ("gemm_f16_f32acc", "gemm_f16_f16acc"):
+        for name in ("gemm_f16_f32acc", "gemm_f16_f16acc", "gemm_f16_f16acc_static_workspace"):
             f = getattr(lib, name)
             f.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
             f.restype = ci
@@ -118,6 +118,11 @@ def gemm_f16_f16acc_workspace_bytes(M, N, K) -> int:
 def gemm_f16_f16acc_workspace(M, N, K, A, lda, B, ldb, C, ldc, workspace, workspace_bytes, stream=0) -> int:
     """gemm_f16_f16acc with caller-provided scratch memory (device, 16-byte aligned) for split-k plans."""
     return load().gemm_f16_f16acc_workspace(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, _ptr(workspace), workspace_bytes, _ptr(stream))
+
+
+def gemm_f16_f16acc_static_workspace(M, N, K, A, lda, B, ldb, C, ldc, stream=0) -> int:
+    """gemm_f16_f16acc_workspace on the library's own fixed scratch array: allocates nothing."""
+    return load().gemm_f16_f16acc_static_workspace(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, _ptr(stream))
 
 
 ACT_NONE, ACT_RELU = 0, 1

@@ -437,6 +437,21 @@ int gemm_f16_f16acc_bias_act(int64_t M, int64_t N, int64_t K, const void* A, int
     return run(1, M, N, K, A, lda, B, ldb, C, ldc, stream, bias, act);
 }
 
+int gemm_f16_f16acc_static_workspace(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                                     const void* B, int64_t ldb, void* C, int64_t ldc, void* stream)
+{
+    const int rc = check_args(1, M, N, K, A, lda, B, ldb, C, ldc);
+    if (rc != GEMM_F16_OK) return rc;
+    const int parts = f16_workspace_parts(M, N, K, A, lda, B, ldb, ldc);
+    if (parts < 2) return run(1, M, N, K, A, lda, B, ldb, C, ldc, stream);      // no scratch memory involved
+    float* ws = nullptr;
+    int64_t floats = 0;
+    const int rc2 = splitk_f16_static_scratch(&ws, &floats);
+    if (rc2 != GEMM_F16_OK) return rc2;
+    if (M * N > floats) return GEMM_F16_ERR_WORKSPACE;
+    return run_f16_split(parts, M, N, K, A, lda, B, ldb, C, ldc, ws, false, false, stream);
+}
+
 const char* gemm_strerror(int code)
 {
     switch (code) {
@@ -447,6 +462,7 @@ const char* gemm_strerror(int code)
     case GEMM_F16_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
     case GEMM_F16_ERR_CONFIG: return "unknown configuration id, activation or bad query argument";
     case GEMM_F16_ERR_ALIGN: return "a pointer is not aligned to its element size";
+    case GEMM_F16_ERR_WORKSPACE: return "the problem needs more scratch memory than the library holds (use gemm_f16_f16acc_workspace or gemm_f16_f16acc)";
     default: return "unknown error code";
     }
 }

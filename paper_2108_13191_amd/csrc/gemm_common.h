@@ -69,6 +69,7 @@ const GemmConfigDesc* deep_ring_config();                             // 128x128
 // gemm_splitk_f16.hip: the passes around a split-k launch in the half-precision mode
 int splitk_f16_zero(float* ws, int64_t n, hipStream_t stream);
 int splitk_f16_finish(float* ws, void* C, int64_t ldc, int64_t M, int64_t N, int clear, hipStream_t stream);
+int splitk_f16_static_scratch(float** ptr, int64_t* floats);            // the library's own scratch memory on the current device
 
 #ifdef GEMM_F16_LADDER
 // Comparison kernels and ablation rows: built into libgemm_f16_ladder.so only, never selected.

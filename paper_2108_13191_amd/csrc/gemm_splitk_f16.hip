@@ -29,7 +29,33 @@ __global__ __launch_bounds__(256) void splitk_finish_f16_kernel(float* __restric
     if (clear) ws[i] = 0.0f;
 }
 
+// The library's own scratch memory for gemm_f16_f16acc_static_workspace: 2^20 floats (4 MB) per
+// GPU the library runs on, held until the process ends; it covers every problem that the
+// workspace form cuts along k.  The name below is a host-side stand-in, not a device address:
+// host code uses the pointer that static_scratch() hands out.
+constexpr int64_t STATIC_SCRATCH_FLOATS = 1 << 20;
+static __device__ __align__(256) float scratch[STATIC_SCRATCH_FLOATS];
+
+constexpr int MAX_DEVICES = 64;
+float* g_scratch_ptr[MAX_DEVICES] = {};
+
 }  // namespace
+
+// The current device's copy of the scratch array (its address is asked for once per device, with
+// that device current) and its size in floats.
+int splitk_f16_static_scratch(float** ptr, int64_t* floats)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return GEMM_F16_ERR_LAUNCH;
+    if (!g_scratch_ptr[dev]) {
+        float* p = nullptr;
+        if (hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return GEMM_F16_ERR_LAUNCH;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    *floats = STATIC_SCRATCH_FLOATS;
+    return GEMM_F16_OK;
+}
 
 // n floats (a multiple of 4, 16-byte aligned) to zero
 int splitk_f16_zero(float* ws, int64_t n, hipStream_t stream)
