@@ -32,7 +32,7 @@ const GemmConfigDesc kGeneric = {
     false, launch_generic, grid_generic};
 
 #ifdef GEMM_F16_LADDER
-constexpr int NUM_LADDER = 11;
+constexpr int NUM_LADDER = 12;
 #else
 constexpr int NUM_LADDER = 0;
 #endif
@@ -64,6 +64,7 @@ const GemmConfigDesc* config(int id)
     case NUM_PRODUCT + 8: return generic_c_in_loop_config();
     case NUM_PRODUCT + 9: return generic_round_per_slice_config();
     case NUM_PRODUCT + 10: return pingpong16_192x192_config();
+    case NUM_PRODUCT + 11: return pingpong16_rowwise_config();
 #endif
     default: return &kGeneric;
     }

@@ -75,6 +75,7 @@ int splitk_f16_static_scratch(float** ptr, int64_t* floats);            // the l
 // Comparison kernels and ablation rows: built into libgemm_f16_ladder.so only, never selected.
 const GemmConfigDesc* pingpong_config();                             // gemm_pingpong.hip: 256x256 on 32x32x16 MFMAs
 const GemmConfigDesc* pingpong16_192x192_config();                   // gemm_pingpong.hip: 192x192 tile (fills 256 compute units where 192x256 fills 192)
+const GemmConfigDesc* pingpong16_rowwise_config();                   // gemm_pingpong.hip: 256x256, MFMAs of a phase row by row of blocks
 const GemmConfigDesc* pingpong16_no_xcd_order_config();              // gemm_pingpong.hip: tiles dealt to XCDs as the hardware deals workgroups
 const GemmConfigDesc* tiled_no_swizzle_config();                     // gemm_tiled.hip: 256x256, LDS image not swizzled
 const GemmConfigDesc* generic_c_in_loop_config();                    // gemm_generic.hip: C read and written in every k step

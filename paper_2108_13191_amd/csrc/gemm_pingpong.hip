@@ -124,7 +124,7 @@ constexpr int pp_lds_bytes() { return 2 * (BM * BK * 2) + 3 * (BK * BN * 2); }  
 // after it, so that a tile's first operands cross the memory system while C is
 // read and written; the epilogue's transposing buffers lie in the LDS that k step
 // 0 does not use.
-template <typename CT, int MI, bool TAIL, int BM, int BN, bool PERSIST = false>
+template <typename CT, int MI, bool TAIL, int BM, int BN, bool PERSIST = false, bool ROWWISE = false>
 __device__ __forceinline__ void pp_tile(const TiledParams& p, const uint32_t smem_base, int m0, int n0,
                                         int next_tile = 0, const int tile_step = 0)
 {
@@ -363,8 +363,10 @@ __device__ __forceinline__ void pp_tile(const TiledParams& p, const uint32_t sme
                     // 1936 TFLOP/s walking row by row (both operands change at every row end), 1960
                     // in serpentine rows, 1985 in this order, 2030 with the same operands every
                     // time; the headline gained 1.3 % from serpentine rows.
+                    // (ROWWISE: a ladder row, the blocks row by row.)
                     const int lin = fm * FN + fn, pr = lin / (2 * FN), q = lin % (2 * FN);
-                    const int gm = 2 * pr + ((q % 4 == 1 || q % 4 == 2) ? 1 : 0), gn = (pr & 1) ? FN - 1 - q / 2 : q / 2;
+                    const int gm = ROWWISE ? fm : 2 * pr + ((q % 4 == 1 || q % 4 == 2) ? 1 : 0);
+                    const int gn = ROWWISE ? fn : (pr & 1) ? FN - 1 - q / 2 : q / 2;
                     if constexpr (MI == 32) acc[gm][gn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[s][gn], fa[s][gm], acc[gm][gn], 0, 0, 0);
                     else                    acc[gm][gn] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fb[s][gn], fa[s][gm], acc[gm][gn], 0, 0, 0);
                     const int idx = (s * FM + fm) * FN + fn;
@@ -584,14 +586,14 @@ inline int late_start_ticks()
 template <int BM, int BN>
 int pp_at_once() { return chip().cus * (pp_lds_bytes<BM, BN>() <= 80 * 1024 ? 2 : 1); }
 
-template <typename CT, int MI, bool TAIL, int BM, int BN>
+template <typename CT, int MI, bool TAIL, int BM, int BN, bool ROWWISE = false>
 __global__ __launch_bounds__(512) void gemm_pp256_kernel(const TiledParams p)
 {
     __shared__ __attribute__((aligned(1024))) char smem[pp_lds_bytes<BM, BN>()];
     late_start(p);
     int tile_m, tile_n;
     tile_of_block(p, blockIdx.x, tile_m, tile_n);
-    pp_tile<CT, MI, TAIL, BM, BN>(p, (uint32_t)(uintptr_t)(lds_ptr_t)smem, tile_m * BM, tile_n * BN);
+    pp_tile<CT, MI, TAIL, BM, BN, false, ROWWISE>(p, (uint32_t)(uintptr_t)(lds_ptr_t)smem, tile_m * BM, tile_n * BN);
 }
 
 // One workgroup per compute unit walks the tiles blockIdx.x, blockIdx.x + gridDim.x,
@@ -742,10 +744,30 @@ const GemmConfigDesc kPingPong16Persistent = {
 // ladder rows: the same kernel on 32x32x16 MFMAs, and with the tiles dealt to the XCDs the way
 // the hardware deals workgroups (no XCD-aware order: the 8 L2s then each see tiles from all over C)
 int launch_pp_no_xcd_order(const GemmArgs& a) { return launch_pp<16, 256, 256>(a, false); }
+// ladder row: the plain 256 x 256 kernel with the MFMAs of a phase issued row by row of blocks
+int launch_pp_rowwise(const GemmArgs& a)
+{
+    const int64_t g = grid_pp<256, 256>(a.M, a.N);
+    if (g < 0) return GEMM_F16_ERR_SIZE;
+    TiledParams p = make_tiled_params(a, 256, 256, 8);
+    p.first_generation = pp_at_once<256, 256>();
+    p.stagger_ticks = (a.K <= 2048 && g >= 4 * (int64_t)p.first_generation) ? late_start_ticks() : 0;     // as launch_pp
+    const bool tail = (a.K % BK) != 0;
+    if (a.c_is_f16) {
+        if (tail) hipLaunchKernelGGL((gemm_pp256_kernel<half_t, 16, true, 256, 256, true>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
+        else      hipLaunchKernelGGL((gemm_pp256_kernel<half_t, 16, false, 256, 256, true>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
+    } else {
+        if (tail) hipLaunchKernelGGL((gemm_pp256_kernel<float, 16, true, 256, 256, true>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
+        else      hipLaunchKernelGGL((gemm_pp256_kernel<float, 16, false, 256, 256, true>), dim3((unsigned)g), dim3(512), 0, a.stream, p);
+    }
+    return hipGetLastError() == hipSuccess ? GEMM_F16_OK : GEMM_F16_ERR_LAUNCH;
+}
 const GemmConfigDesc kPingPong = {
     "pp256x256x64_w2x4", 256, 256, BK, 8, 128, 64, lds_pp(256, 256), true, launch_pp_plain<32, 256, 256>, grid_pp<256, 256>};
 const GemmConfigDesc kPingPong16_192x192 = {
     "pp192x192x64_w2x4_mi16", 192, 192, BK, 8, 96, 48, lds_pp(192, 192), true, launch_pp_plain<16, 192, 192>, grid_pp<192, 192>};
+const GemmConfigDesc kPingPong16Rowwise = {
+    "pp256x256x64_w2x4_mi16_rowwise", 256, 256, BK, 8, 128, 64, lds_pp(256, 256), true, launch_pp_rowwise, grid_pp<256, 256>};
 const GemmConfigDesc kPingPong16NoXcd = {
     "pp256x256x64_w2x4_mi16_noxcd", 256, 256, BK, 8, 128, 64, lds_pp(256, 256), true, launch_pp_no_xcd_order, grid_pp<256, 256>};
 #endif
@@ -764,4 +786,5 @@ const GemmConfigDesc* pingpong16_config(int bm, int bn)
 const GemmConfigDesc* pingpong_config() { return &kPingPong; }
 const GemmConfigDesc* pingpong16_no_xcd_order_config() { return &kPingPong16NoXcd; }
 const GemmConfigDesc* pingpong16_192x192_config() { return &kPingPong16_192x192; }
+const GemmConfigDesc* pingpong16_rowwise_config() { return &kPingPong16Rowwise; }
 #endif

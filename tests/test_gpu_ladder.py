@@ -18,7 +18,7 @@ from gpu_util import run_gemm, assert_close, config_id       # noqa: E402
 
 CDT = {"f32": np.float32, "f16": np.float16}
 ROWS = ["t128x128x64_w2x2", "t256x256x64_w2x4", "t256x256x64_w2x4_noswz", "pp256x256x64_w2x4",
-        "pp256x256x64_w2x4_mi16_noxcd", "pp192x192x64_w2x4_mi16", "w4_256x256x64", "il256x256x64_w2x4_mi16", "generic64x64x32_c_in_loop",
+        "pp256x256x64_w2x4_mi16_noxcd", "pp192x192x64_w2x4_mi16", "pp256x256x64_w2x4_mi16_rowwise", "w4_256x256x64", "il256x256x64_w2x4_mi16", "generic64x64x32_c_in_loop",
         "generic64x64x32_f16_round_per_slice"]
 SHAPES = [(64, 64, 64), (300, 264, 200), (520, 776, 136), (257, 8, 8), (1, 520, 72), (130, 136, 1000),
           (513, 264, 64), (256, 256, 8), (1100, 1296, 448)]
