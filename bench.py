@@ -190,6 +190,12 @@ def time_gemm(binding, torch, mode, M, N, K, sets, steps, warmup):
     fn = binding.gemm_f16_f32acc if mode == "f32" else binding.gemm_f16_f16acc
     stream = torch.cuda.current_stream()
     sp = stream.cuda_stream
+    if mode == "f16ws":         # the f16 mode with M x N floats of lent scratch memory (skinny problems: split k)
+        ws_bytes = max(binding.gemm_f16_f16acc_workspace_bytes(M, N, K), 16)
+        ws = torch.empty(ws_bytes // 4, dtype=torch.float32, device=sets[0][0].device)
+
+        def fn(M, N, K, a, lda, b, ldb, c, ldc, sp):
+            return binding.gemm_f16_f16acc_workspace(M, N, K, a, lda, b, ldb, c, ldc, ws, ws_bytes, sp)
     dA, dB, dC = sets[0]
     lda, ldb, ldc = dA.stride(0), dB.stride(0), dC.stride(0)
     R = len(sets)
@@ -313,7 +319,9 @@ def main():
         M, N, K, mode, sets = prep["M"], prep["N"], prep["K"], prep["mode"], prep["sets"]
         ms, per, wall = time_gemm(binding, torch, mode, M, N, K, sets, steps, warmup)
         dA, dB, dC = sets[0]
-        cfg = binding.query_config(mode == "f16", M, N, K, dA, dA.stride(0), dB, dB.stride(0), dC, dC.stride(0))
+        cfg = binding.query_config(mode != "f32", M, N, K, dA, dA.stride(0), dB, dB.stride(0), dC, dC.stride(0))
+        if mode == "f16ws" and binding.gemm_f16_f16acc_workspace_bytes(M, N, K) > 0:
+            cfg["name"] = "w4a_128x128x64, k loop in parts through a workspace of M x N floats"
         flops = 2.0 * M * N * K
         if cfg.get("split_rows"):
             cfg["plan"] = f"{cfg['name']} on rows 0..{cfg['split_rows'] - 1} + {binding.describe_config(cfg['id2'])['name']} on the rest"
@@ -449,6 +457,8 @@ def main():
         for name, (m, n, k, _, _, modes) in wl.WORKLOADS.items():
             for mode in modes:
                 point(name, name, mode, m, n, k)
+                if mode == "f16" and binding.gemm_f16_f16acc_workspace_bytes(m, n, k) > 0:
+                    point(name, name, "f16ws", m, n, k)           # gemm_f16_f16acc_workspace on the same problem
         for n in wl.SQUARE_SWEEP:
             for mode in ("f32", "f16"):
                 point(f"square{n}", None, mode, n, n, n, shape=(n, n, n))
