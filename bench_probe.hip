@@ -64,39 +64,40 @@ __global__ __launch_bounds__(512) void mfma_only_kernel(const half8* __restrict_
 // Registers: v[0:31] A fragments, v[34:49] B fragments, v[64:191] accumulators, v[200:215] read
 // targets, v230 / v231 LDS read addresses, v232 the lane's copy offset.
 #define MFMA(c0, c1, b0, b1, a0, a1) "v_mfma_f32_16x16x32_f16 v[" #c0 ":" #c1 "], v[" #b0 ":" #b1 "], v[" #a0 ":" #a1 "], v[" #c0 ":" #c1 "]\n\t"
+// (the 32 MFMAs in the order of the library's kernels: two rows of blocks at a time, down, right, up, right)
 #define LOOP_BODY(R0, R1, R2, R3, R4, R5, R6, R7, R8, R9, R10, R11, R12, R13, R14, R15, S0, S1, S2, S3, G0, G1, G2, G3) \
     MFMA(64, 67, 34, 37, 0, 3) \
-    MFMA(68, 71, 38, 41, 0, 3) R0 \
-    MFMA(72, 75, 42, 45, 0, 3) \
-    MFMA(76, 79, 46, 49, 0, 3) R1 S0 \
-    MFMA(80, 83, 34, 37, 4, 7) G0 \
-    MFMA(84, 87, 38, 41, 4, 7) R2 \
-    MFMA(88, 91, 42, 45, 4, 7) \
-    MFMA(92, 95, 46, 49, 4, 7) R3 \
-    MFMA(96, 99, 34, 37, 8, 11) \
-    MFMA(100, 103, 38, 41, 8, 11) R4 \
-    MFMA(104, 107, 42, 45, 8, 11) \
-    MFMA(108, 111, 46, 49, 8, 11) R5 S1 \
-    MFMA(112, 115, 34, 37, 12, 15) G1 \
-    MFMA(116, 119, 38, 41, 12, 15) R6 \
+    MFMA(80, 83, 34, 37, 4, 7) R0 \
+    MFMA(84, 87, 38, 41, 4, 7) \
+    MFMA(68, 71, 38, 41, 0, 3) R1 S0 \
+    MFMA(72, 75, 42, 45, 0, 3) G0 \
+    MFMA(88, 91, 42, 45, 4, 7) R2 \
+    MFMA(92, 95, 46, 49, 4, 7) \
+    MFMA(76, 79, 46, 49, 0, 3) R3 \
+    MFMA(108, 111, 46, 49, 8, 11) \
+    MFMA(124, 127, 46, 49, 12, 15) R4 \
     MFMA(120, 123, 42, 45, 12, 15) \
-    MFMA(124, 127, 46, 49, 12, 15) R7 \
+    MFMA(104, 107, 42, 45, 8, 11) R5 S1 \
+    MFMA(100, 103, 38, 41, 8, 11) G1 \
+    MFMA(116, 119, 38, 41, 12, 15) R6 \
+    MFMA(112, 115, 34, 37, 12, 15) \
+    MFMA(96, 99, 34, 37, 8, 11) R7 \
     MFMA(128, 131, 34, 37, 16, 19) \
-    MFMA(132, 135, 38, 41, 16, 19) R8 \
-    MFMA(136, 139, 42, 45, 16, 19) \
-    MFMA(140, 143, 46, 49, 16, 19) R9 S2 \
-    MFMA(144, 147, 34, 37, 20, 23) G2 \
-    MFMA(148, 151, 38, 41, 20, 23) R10 \
-    MFMA(152, 155, 42, 45, 20, 23) \
-    MFMA(156, 159, 46, 49, 20, 23) R11 \
-    MFMA(160, 163, 34, 37, 24, 27) \
-    MFMA(164, 167, 38, 41, 24, 27) R12 \
-    MFMA(168, 171, 42, 45, 24, 27) \
-    MFMA(172, 175, 46, 49, 24, 27) R13 S3 \
-    MFMA(176, 179, 34, 37, 28, 31) G3 \
-    MFMA(180, 183, 38, 41, 28, 31) R14 \
+    MFMA(144, 147, 34, 37, 20, 23) R8 \
+    MFMA(148, 151, 38, 41, 20, 23) \
+    MFMA(132, 135, 38, 41, 16, 19) R9 S2 \
+    MFMA(136, 139, 42, 45, 16, 19) G2 \
+    MFMA(152, 155, 42, 45, 20, 23) R10 \
+    MFMA(156, 159, 46, 49, 20, 23) \
+    MFMA(140, 143, 46, 49, 16, 19) R11 \
+    MFMA(172, 175, 46, 49, 24, 27) \
+    MFMA(188, 191, 46, 49, 28, 31) R12 \
     MFMA(184, 187, 42, 45, 28, 31) \
-    MFMA(188, 191, 46, 49, 28, 31) R15
+    MFMA(168, 171, 42, 45, 24, 27) R13 S3 \
+    MFMA(164, 167, 38, 41, 24, 27) G3 \
+    MFMA(180, 183, 38, 41, 28, 31) R14 \
+    MFMA(176, 179, 34, 37, 28, 31) \
+    MFMA(160, 163, 34, 37, 24, 27) R15
 
 #define LOOP_MFMA_ONLY LOOP_BODY("", "", "", "", "", "", "", "", "", "", "", "", "", "", "", "", "", "", "", "", "", "", "", "")
 #define LOOP_LDS LOOP_BODY("ds_read_b128 v[200:203], v230 offset:0\n\t", "ds_read_b64_tr_b16 v[204:205], v231 offset:1024\n\t", "ds_read_b128 v[208:211], v230 offset:2048\n\t", "ds_read_b64_tr_b16 v[212:213], v231 offset:3072\n\t", "ds_read_b128 v[200:203], v230 offset:4096\n\t", "ds_read_b64_tr_b16 v[204:205], v231 offset:5120\n\t", "ds_read_b128 v[208:211], v230 offset:6144\n\t", "ds_read_b64_tr_b16 v[212:213], v231 offset:7168\n\t", "ds_read_b128 v[200:203], v230 offset:8192\n\t", "ds_read_b64_tr_b16 v[204:205], v231 offset:9216\n\t", "ds_read_b128 v[208:211], v230 offset:10240\n\t", "ds_read_b64_tr_b16 v[212:213], v231 offset:11264\n\t", "ds_read_b128 v[200:203], v230 offset:12288\n\t", "ds_read_b64_tr_b16 v[204:205], v231 offset:13312\n\t", "ds_read_b128 v[208:211], v230 offset:14336\n\t", "ds_read_b64_tr_b16 v[212:213], v231 offset:15360\n\t", "", "", "", "", "", "", "", "") "s_waitcnt lgkmcnt(0)"
