@@ -74,7 +74,8 @@ enum {
  * Skinny problems (at most half as many 128 x 128 tiles as compute units, K >=
  * 2048, M*N small) run with the k loop cut into parts: C is not read, every
  * part adds its sum to the C in memory with hardware f32 atomic additions
- * (C0 + part + part + ...).  Their order is not fixed, so that two runs may
+ * (C0 + part + part + ...; a part that is exactly zero adds nothing, so a C
+ * that gets no contribution keeps its bits).  Their order is not fixed, so that two runs may
  * differ in the last bits (never where the sums are exact), and C must lie in
  * ordinary device memory (hipMalloc: memory on which the device's
  * floating-point atomics work).  gemm_f16_query_config reports such a plan by

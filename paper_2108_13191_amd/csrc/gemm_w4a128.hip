@@ -249,7 +249,8 @@ __global__ __launch_bounds__(256) void gemm_w4a128_kernel(const TiledParams p)
             float* const cbase = reinterpret_cast<float*>(Cbase) + (int64_t)c_row0 * p.ldc + c_col0 + lane;
             for (int r = 0; r < rows_in; r++) {
                 const float v = *(__attribute__((address_space(3))) const float*)(uintptr_t)(tbuf + (uint32_t)r * T_PITCH + 4u * lane);
-                if (col_in) unsafeAtomicAdd(cbase + (int64_t)r * p.ldc, v);
+                // a part that sums to zero leaves C alone (the memory's adders need not keep a subnormal C + 0)
+                if (col_in && v != 0.0f) unsafeAtomicAdd(cbase + (int64_t)r * p.ldc, v);
             }
             return;
         }

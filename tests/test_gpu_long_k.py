@@ -153,6 +153,20 @@ def test_split_k_plans_of_skinny_problems(oracle_mod):
     assert np.array_equal(dC.fetch(), np.maximum(oracle_mod.round_to_f32(Cref) + bias[None, :], 0).astype(np.float32))
 
 
+def test_split_k_leaves_special_values_of_c_alone():
+    """Parts that sum to zero do not touch C: subnormal f32 values, signed zeros, infinities and
+    NaN in C come back bit for bit from a split-k problem whose product is zero."""
+    M, N, K = 64, 520, 4096
+    assert binding.query_config(False, M, N, K, 16, K, 16, N, 16, N)["grid"] > ((M + 127) // 128) * ((N + 127) // 128)
+    A = np.zeros((M, K), np.float16)
+    B = wl.make_inputs(M, N, K, "uniform", "zeros", seed=5)[1]
+    C0 = np.zeros((M, N), np.float32)
+    C0.view(np.uint32)[:] = np.random.default_rng(3).integers(0, 1 << 20, size=(M, N), dtype=np.uint32)      # subnormals
+    C0[0, :6] = [np.inf, -np.inf, np.nan, -0.0, 0.0, np.float32(1e-45)]
+    got = run_gemm(A, B, C0, "f32")
+    assert np.array_equal(got.view(np.uint32), C0.view(np.uint32))
+
+
 def test_half_precision_mode_with_a_workspace(oracle_mod):
     """gemm_f16_f16acc_workspace: with M x N floats of scratch memory the skinny problems that the
     f32 mode cuts along k are cut in the f16 mode too (the parts add to the zeroed workspace, a last
