@@ -167,6 +167,37 @@ def test_split_k_leaves_special_values_of_c_alone():
     assert np.array_equal(got.view(np.uint32), C0.view(np.uint32))
 
 
+def test_split_k_propagates_nan_and_infinities(oracle_mod):
+    """Infinities and NaN in A, B and C reach the same results through a split k loop as through
+    one pass: the class of every result (finite, +inf, -inf, NaN) equals the oracle's, the finite
+    ones are within tolerance."""
+    M, N, K = 100, 520, 4096
+    A, B, C0 = wl.make_inputs(M, N, K, "uniform", "uniform", seed=77)
+    A[5, 17] = np.nan                    # a NaN row of results
+    A[40, 4095] = np.inf                 # in the last part: +-inf by the sign of B[4095, j]
+    B[0, 7] = -np.inf                    # a column: -inf * A[i, 0] (first part)
+    A[41, 3] = np.inf
+    B[3, 9] = 0.0                        # inf * 0 = NaN at (41, 9)
+    A[42, 10] = np.inf
+    A[42, 3000] = -np.inf                # +inf from one part, -inf from another: NaN in the columns where B has one sign in both rows
+    C0[77, 100] = np.inf
+    C0[78, 101] = np.nan
+    got = run_gemm(A, B, C0, "f32")
+    with np.errstate(invalid="ignore", over="ignore"):
+        Cref, S = oracle_mod.gemm_f16(A, B, C0)
+
+    def cls(x):
+        x = np.asarray(x, dtype=np.float64)
+        return np.where(np.isnan(x), 3, np.where(np.isposinf(x), 1, np.where(np.isneginf(x), 2, 0)))
+    want_cls, got_cls = cls(Cref), cls(got)
+    assert np.array_equal(got_cls, want_cls), np.argwhere(got_cls != want_cls)[:5]
+    assert want_cls[5].min() == 3 and want_cls[41, 9] == 3 and want_cls[77, 100] == 1 and (want_cls[42] == 3).any()
+    fin = want_cls == 0
+    with np.errstate(invalid="ignore"):
+        err = np.abs(got.astype(np.float64) - Cref)[fin]
+    assert np.all(err <= (1e-5 * (S + np.abs(C0.astype(np.float64))))[fin])
+
+
 def test_half_precision_mode_with_a_workspace(oracle_mod):
     """gemm_f16_f16acc_workspace: with M x N floats of scratch memory the skinny problems that the
     f32 mode cuts along k are cut in the f16 mode too (the parts add to the zeroed workspace, a last
