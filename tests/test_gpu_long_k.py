@@ -153,6 +153,38 @@ def test_split_k_plans_of_skinny_problems(oracle_mod):
     assert np.array_equal(dC.fetch(), np.maximum(oracle_mod.round_to_f32(Cref) + bias[None, :], 0).astype(np.float32))
 
 
+def test_split_k_on_random_skinny_shapes(oracle_mod):
+    """Seeded random skinny problems (1 to 500 rows, 8 to 2048 columns, K up to 16384 with and without
+    a k tail) under automatic selection, f32 mode and the f16 mode with a workspace: sampled rows
+    against the oracle, integers bit for bit; most of them run with a split k loop."""
+    rng = np.random.default_rng(4242)
+    split = 0
+    for idx in range(14):
+        M = int(rng.integers(1, 500))
+        N = int(rng.integers(1, 257)) * 8
+        K = int(rng.integers(256, 2049)) * 8
+        tiles = ((M + 127) // 128) * ((N + 127) // 128)
+        q = binding.query_config(False, M, N, K, 16, K, 16, N, 16, N)
+        split += q["name"] == NAME128 and q["grid"] > tiles
+        A, B, _ = wl.make_inputs(M, N, K, "int2", "zeros", seed=1400 + idx)
+        C0 = rng.integers(-4, 5, size=(M, N)).astype(np.float32)
+        rows = np.unique(np.concatenate([[0, M - 1], rng.integers(0, M, size=min(M, 12))]))
+        Cref, _ = oracle_mod.gemm_f16(A, B, C0, rows=rows)
+        got = run_gemm(A, B, C0, "f32")
+        assert np.array_equal(got[rows], oracle_mod.round_to_f32(Cref)), f"f32 {(M, N, K)} {q['name']} grid {q['grid']}"
+        # the f16 mode through the workspace entry point (also where no workspace is needed)
+        from gpu_util import DevMat
+        C16 = C0.astype(np.float16)
+        need = binding.gemm_f16_f16acc_workspace_bytes(M, N, K)
+        ws = torch.full((max(need // 4, 4),), float("nan"), device="cuda")
+        dA, dB, dC = DevMat(A, nan_canary=True), DevMat(B, nan_canary=True), DevMat(C16)
+        binding.check(binding.gemm_f16_f16acc_workspace(M, N, K, dA.ptr, dA.ld, dB.ptr, dB.ld, dC.ptr, dC.ld, ws, need, 0))
+        torch.cuda.synchronize()
+        Cref16, _ = oracle_mod.gemm_f16(A, B, C16, rows=rows)
+        assert np.array_equal(dC.fetch()[rows], Cref16.astype(np.float16)), f"f16 workspace {(M, N, K)} need {need}"
+    assert split >= 8, split
+
+
 def test_split_k_leaves_special_values_of_c_alone():
     """Parts that sum to zero do not touch C: subnormal f32 values, signed zeros, infinities and
     NaN in C come back bit for bit from a split-k problem whose product is zero."""
